@@ -1,0 +1,167 @@
+/*
+ * adacomp.h -- C ABI of the MI355X (gfx950) implementation of AdaComp's
+ * data-parallel hot path.
+ *
+ *   worker side            adacomp_select()  SELECT_GRAD of Alg. 1: per tensor (each
+ *                                            weight matrix V_l and bias vector beta_l
+ *                                            on its own), keep the (100*c)% entries
+ *                                            largest in absolute value
+ *   parameter-server side  adacomp_apply()   loop body of Alg. 2 for a queue of
+ *                                            received updates: per-parameter staleness
+ *                                            (eq. 3), learning rate alpha/sigma_k
+ *                                            (eq. 5), parameter step (eq. 4)
+ *
+ * Conventions common to all calls
+ *   - "DEVICE" pointers are HIP device memory of the current device, "HOST" pointers
+ *     ordinary host memory.  Every buffer is allocated and owned by the caller; the
+ *     library allocates no device memory, keeps no global state and never
+ *     synchronises the device.  All device work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and is complete
+ *     when that stream has drained.  Host arrays are read before the call returns.
+ *   - Return value 0 on success, a negative ADACOMP_ERR_* otherwise.  Arguments are
+ *     checked before anything is enqueued: a failing call has no side effect.
+ *   - Sizes are in elements unless a name says bytes.  A tensor has at most
+ *     2^32 - 1 elements.  Zero-element tensors are legal.
+ */
+#ifndef ADACOMP_H
+#define ADACOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ADACOMP_OK = 0,
+    ADACOMP_ERR_NULL = -1,            /* a required pointer is NULL                          */
+    ADACOMP_ERR_RATE = -2,            /* rate is NaN or outside [0, 1]                       */
+    ADACOMP_ERR_LAYER_TOO_LARGE = -3, /* a tensor has 2^32 or more elements                  */
+    ADACOMP_ERR_CAPACITY = -4,        /* update buffers hold fewer than sum_l k_l entries    */
+    ADACOMP_ERR_WORKSPACE = -5,       /* workspace NULL, misaligned (256 B) or too small     */
+    ADACOMP_ERR_LAYER_MISMATCH = -6,  /* update / state tensor count or sizes differ from params */
+    ADACOMP_ERR_FUTURE_PULL = -7,     /* an update's pull_ts is later than its apply time    */
+    ADACOMP_ERR_K_RANGE = -8,         /* k_override[l] > n_l                                 */
+    ADACOMP_ERR_HISTORY = -9,         /* pull_ts precedes the first update of this call      */
+    ADACOMP_ERR_LR = -10,             /* learning rate is not finite                         */
+    ADACOMP_ERR_ALIGNMENT = -11,      /* a float/uint32 device pointer is not 4-byte aligned */
+    ADACOMP_ERR_HIP = -12             /* a HIP runtime call (kernel launch) failed           */
+};
+
+/* One tensor of a worker's dense update Delta Theta^(w): a V_l or a beta_l
+ * (Sec. 4 "Selection method").  data: DEVICE, n floats, read only. */
+typedef struct {
+    const float *data;
+    uint64_t n;
+} adacomp_layer_t;
+
+/* The slice of Theta that corresponds to one tensor; data: DEVICE, n floats,
+ * updated in place by adacomp_apply (eq. 4). */
+typedef struct {
+    float *data;
+    uint64_t n;
+} adacomp_param_layer_t;
+
+/* A compressed update Delta~Theta^(w) (Table 1; Alg. 1 lines "SELECT_GRAD" and
+ * "Push") together with the timestamp the worker pulled.  The paper leaves the
+ * encoding open (footnote of Sec. 4); here: per tensor, the selected entries as
+ * (index within the tensor, value) pairs in strictly ascending index order, the
+ * tensors laid end to end, structure-of-arrays.
+ *   layer_off      HOST   [num_layers+1]  entries of tensor l are [off[l], off[l+1])
+ *   layer_off_dev  DEVICE [num_layers+1]  the same numbers, for the kernels
+ *   idx            DEVICE [cap]           uint32 index local to the tensor
+ *   val            DEVICE [cap]           value, bit-identical to the dense entry
+ *   cap                                   capacity of idx/val in entries
+ *   pull_ts                               j: PS timestamp the worker fetched (Alg. 1
+ *                                         "Pull"); not touched by adacomp_select
+ * adacomp_select fills layer_off, layer_off_dev, idx, val.  adacomp_apply reads all. */
+typedef struct {
+    uint32_t num_layers;
+    uint64_t *layer_off;
+    uint64_t *layer_off_dev;
+    uint32_t *idx;
+    float *val;
+    uint64_t cap;
+    uint64_t pull_ts;
+} adacomp_update_t;
+
+/* Parameter-server staleness state (Alg. 2; Sec. 4 "Algorithm details": the PS
+ * keeps a timestamp and a trace of received updates).  Caller-owned memory whose
+ * contents the library defines; zero-initialise for a fresh server.
+ *   t     i: number of updates applied so far (advanced by adacomp_apply)
+ *   cnt   HOST array [num_layers] of DEVICE pointers; cnt[l][k] (uint32, n_l of
+ *         them) = number of applied updates whose entry for parameter k of tensor l
+ *         was non-zero.  sigma_k of eq. 3 is a difference of two readings of it. */
+typedef struct {
+    uint64_t t;
+    uint32_t num_layers;
+    uint32_t **cnt;
+} adacomp_state_t;
+
+/* k_l: how many entries "(100*c)%" of an n-entry tensor means (Alg. 1,
+ * SELECT_GRAD; c = rate in [0,1], Table 1).  The paper states no rounding:
+ * 0 if rate == 0 or n == 0; n if rate == 1; otherwise
+ * min(n, max(1, ceil((rate*n) * (1 - 2^-40)))) in IEEE double.  Returns 0 for an
+ * invalid rate.  Pure host function. */
+uint64_t adacomp_count(uint64_t n, double rate);
+
+/* Bytes of DEVICE workspace adacomp_select needs for tensors of sizes n[0..L) at
+ * `rate` (k_override as in adacomp_select).  Depends only on these arguments,
+ * never on data.  HOST pointers.  Pure host function. */
+int adacomp_select_workspace(const uint64_t *n, uint32_t L, double rate,
+                             const uint64_t *k_override, size_t *bytes);
+
+/* SELECT_GRAD (Alg. 1): for each of the L tensors keep the k_l entries of largest
+ * magnitude, k_l = k_override[l] if k_override != NULL else adacomp_count(n_l, rate).
+ * Magnitudes are compared exactly (IEEE bit pattern without the sign: denormals
+ * are not flushed, +x ties -x, +-0 are the smallest, NaN patterns order above
+ * infinity); among equal magnitudes the lower index is kept.  Exactly k_l entries
+ * are produced per tensor, explicit zeros included if k_l exceeds the number of
+ * non-zeros.
+ *   layers      HOST [L]; layers[l].data DEVICE
+ *   k_override  HOST [L] or NULL
+ *   out         HOST struct; out->num_layers must equal L; out->layer_off (HOST,
+ *               L+1) is filled before the call returns, since k_l does not depend
+ *               on the data; out->layer_off_dev, idx, val (DEVICE) are filled by the
+ *               enqueued kernels; out->cap >= sum_l k_l
+ *   workspace   DEVICE, 256-byte aligned, >= adacomp_select_workspace() bytes;
+ *               contents are scratch, may be reused by the next call on the same stream
+ * Calls sharing a workspace must be on the same stream. */
+int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double rate,
+                   const uint64_t *k_override, adacomp_update_t *out,
+                   void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Bytes of DEVICE workspace adacomp_apply needs for a queue of Q updates (HOST
+ * array; only num_layers and layer_off are read) on L parameter tensors. */
+int adacomp_apply_workspace(uint32_t L, const adacomp_update_t *updates, uint32_t Q,
+                            size_t *bytes);
+
+/* Parameter-server iterations (Alg. 2, loop body) for a queue: updates[0..Q) are
+ * applied in array order as iterations i = st->t, st->t + 1, ...; for each entry
+ * (k, v) of update q with pull timestamp j:
+ *     sigma_k = #{ u in [j, i-1] : update u had a non-zero entry for k }   (eq. 3)
+ *     alpha_k = lr / sigma_k if sigma_k != 0 else lr                        (eq. 5)
+ *     Theta_k = Theta_k - alpha_k * v                                       (eq. 4)
+ * in fp32, as one correctly rounded divide, one multiply and one subtract.  An
+ * entry counts as non-zero iff its value is not +-0.  An empty update still
+ * advances the timestamp.  On success st->t += Q (at enqueue time).
+ *   params   HOST [L]; data DEVICE, updated in place
+ *   st       HOST struct; st->num_layers == L; st->cnt HOST [L] of DEVICE pointers
+ *   updates  HOST [Q]; each must have num_layers == L, idx < n_l, strictly ascending
+ *            per tensor (malformed index lists are undefined behaviour);
+ *            st->t <= pull_ts <= apply time of that update, else
+ *            ADACOMP_ERR_HISTORY / ADACOMP_ERR_FUTURE_PULL
+ *   lr       alpha, finite
+ *   workspace DEVICE, 256-byte aligned, >= adacomp_apply_workspace() bytes */
+int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, adacomp_state_t *st,
+                  const adacomp_update_t *updates, uint32_t Q, float lr,
+                  void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Static, human-readable text for a return code. */
+const char *adacomp_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADACOMP_H */

@@ -1,0 +1,19 @@
+"""MI355X (gfx950) implementation of AdaComp's data-parallel hot path.
+
+Thin ctypes binding over libadacomp.so (C ABI in include/adacomp.h).  All
+computation happens in the library's HIP kernels; this package only marshals
+arguments.  PyTorch is used to own device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    AdaCompError,
+    Update,
+    State,
+    adacomp_count,
+    adacomp_select_workspace,
+    adacomp_select,
+    adacomp_apply_workspace,
+    adacomp_apply,
+    adacomp_strerror,
+    library_path,
+    load_library,
+)

@@ -1,0 +1,199 @@
+"""Argument marshalling between torch tensors and the C ABI of libadacomp.so.
+
+Nothing here computes anything of the method: no selection, no staleness, no
+parameter arithmetic.  If the shared library is missing the calls raise; there is
+no fallback path.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libadacomp.so")
+_lib = None
+
+
+class AdaCompError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {adacomp_strerror(code)} ({code})")
+
+
+class _Layer(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("n", C.c_uint64)]
+
+
+class _Update(C.Structure):
+    _fields_ = [("num_layers", C.c_uint32),
+                ("layer_off", C.POINTER(C.c_uint64)),
+                ("layer_off_dev", C.c_void_p),
+                ("idx", C.c_void_p),
+                ("val", C.c_void_p),
+                ("cap", C.c_uint64),
+                ("pull_ts", C.c_uint64)]
+
+
+class _State(C.Structure):
+    _fields_ = [("t", C.c_uint64), ("num_layers", C.c_uint32), ("cnt", C.POINTER(C.c_void_p))]
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libadacomp.so built in-tree (python -m paper_1702_04683_amd.build or
+    __graft_entry__.build()).  Raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build the HIP library first "
+                          "(python __graft_entry__.py build)")
+    lib = C.CDLL(_LIB_PATH)
+    u64, u32, vp, sz = C.c_uint64, C.c_uint32, C.c_void_p, C.c_size_t
+    lib.adacomp_count.restype = u64
+    lib.adacomp_count.argtypes = [u64, C.c_double]
+    lib.adacomp_select_workspace.restype = C.c_int
+    lib.adacomp_select_workspace.argtypes = [C.POINTER(u64), u32, C.c_double, C.POINTER(u64), C.POINTER(sz)]
+    lib.adacomp_select.restype = C.c_int
+    lib.adacomp_select.argtypes = [C.POINTER(_Layer), u32, C.c_double, C.POINTER(u64), C.POINTER(_Update),
+                                   vp, sz, vp]
+    lib.adacomp_apply_workspace.restype = C.c_int
+    lib.adacomp_apply_workspace.argtypes = [u32, C.POINTER(_Update), u32, C.POINTER(sz)]
+    lib.adacomp_apply.restype = C.c_int
+    lib.adacomp_apply.argtypes = [C.POINTER(_Layer), u32, C.POINTER(_State), C.POINTER(_Update), u32,
+                                  C.c_float, vp, sz, vp]
+    lib.adacomp_strerror.restype = C.c_char_p
+    lib.adacomp_strerror.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def _u64_array(values):
+    return (C.c_uint64 * max(len(values), 1))(*[int(v) for v in values])
+
+
+def _stream_ptr(stream, device):
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    return C.c_void_p(stream.cuda_stream)
+
+
+class Update:
+    """Device buffers of one compressed update (adacomp_update_t)."""
+
+    def __init__(self, num_layers, cap, device, pull_ts=0):
+        self.num_layers = int(num_layers)
+        self.cap = int(cap)
+        self.pull_ts = int(pull_ts)
+        self.layer_off = (C.c_uint64 * (self.num_layers + 1))()
+        self.layer_off_dev = torch.zeros(self.num_layers + 1, dtype=torch.int64, device=device)
+        self.idx = torch.empty(max(self.cap, 1), dtype=torch.int32, device=device)   # uint32 bit patterns
+        self.val = torch.empty(max(self.cap, 1), dtype=torch.float32, device=device)
+
+    @property
+    def offsets(self):
+        return [int(x) for x in self.layer_off]
+
+    @property
+    def total(self):
+        return int(self.layer_off[self.num_layers])
+
+    def c_struct(self):
+        return _Update(self.num_layers, C.cast(self.layer_off, C.POINTER(C.c_uint64)),
+                       self.layer_off_dev.data_ptr(), self.idx.data_ptr(), self.val.data_ptr(),
+                       self.cap, self.pull_ts)
+
+    @classmethod
+    def from_host(cls, layer_off, idx, val, device, pull_ts=0):
+        """Upload an update given as host arrays (what a PS would receive from the wire)."""
+        L = len(layer_off) - 1
+        u = cls(L, int(layer_off[-1]), device, pull_ts)
+        for l in range(L + 1):
+            u.layer_off[l] = int(layer_off[l])
+        u.layer_off_dev.copy_(torch.as_tensor([int(x) for x in layer_off], dtype=torch.int64))
+        if u.cap:
+            import numpy as np
+            u.idx[:u.cap].copy_(torch.from_numpy(np.ascontiguousarray(idx, dtype=np.uint32).view(np.int32)))
+            u.val[:u.cap].copy_(torch.from_numpy(np.ascontiguousarray(val, dtype=np.float32)))
+        return u
+
+
+class State:
+    """Parameter-server staleness state (adacomp_state_t): timestamp and per-parameter counters."""
+
+    def __init__(self, params):
+        self.cnt = [torch.zeros(max(p.numel(), 1), dtype=torch.int32, device=p.device) for p in params]
+        self._cnt_ptrs = (C.c_void_p * max(len(params), 1))(*[c.data_ptr() for c in self.cnt])
+        self._c = _State(0, len(params), C.cast(self._cnt_ptrs, C.POINTER(C.c_void_p)))
+
+    @property
+    def t(self):
+        return int(self._c.t)
+
+    @t.setter
+    def t(self, v):
+        self._c.t = int(v)
+
+
+def adacomp_strerror(code):
+    return load_library().adacomp_strerror(int(code)).decode()
+
+
+def adacomp_count(n, rate):
+    return int(load_library().adacomp_count(int(n), float(rate)))
+
+
+def adacomp_select_workspace(sizes, rate, k_override=None):
+    out = C.c_size_t(0)
+    kov = _u64_array(k_override) if k_override is not None else None
+    rc = load_library().adacomp_select_workspace(_u64_array(sizes), len(sizes), float(rate), kov, C.byref(out))
+    if rc:
+        raise AdaCompError(rc, "adacomp_select_workspace")
+    return int(out.value)
+
+
+def _layers(tensors):
+    arr = (_Layer * max(len(tensors), 1))()
+    for l, t in enumerate(tensors):
+        if t.dtype != torch.float32 or not t.is_contiguous():
+            raise TypeError("tensors must be contiguous float32")
+        arr[l].data = t.data_ptr() if t.numel() else None
+        arr[l].n = t.numel()
+    return arr
+
+
+def adacomp_select(layers, rate, out, workspace, k_override=None, stream=None):
+    """SELECT_GRAD on a list of device tensors into `out` (an Update).  Asynchronous."""
+    dev = workspace.device
+    kov = _u64_array(k_override) if k_override is not None else None
+    cu = out.c_struct()
+    rc = load_library().adacomp_select(_layers(layers), len(layers), float(rate), kov, C.byref(cu),
+                                       workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                       _stream_ptr(stream, dev))
+    if rc:
+        raise AdaCompError(rc, "adacomp_select")
+    return out
+
+
+def adacomp_apply_workspace(num_layers, updates):
+    out = C.c_size_t(0)
+    arr = (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
+    rc = load_library().adacomp_apply_workspace(int(num_layers), arr, len(updates), C.byref(out))
+    if rc:
+        raise AdaCompError(rc, "adacomp_apply_workspace")
+    return int(out.value)
+
+
+def adacomp_apply(params, state, updates, lr, workspace, stream=None):
+    """Apply a queue of Updates to the parameter tensors in place.  Asynchronous."""
+    dev = workspace.device
+    arr = (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
+    rc = load_library().adacomp_apply(_layers(params), len(params), C.byref(state._c), arr, len(updates),
+                                      float(lr), workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream_ptr(stream, dev))
+    if rc:
+        raise AdaCompError(rc, "adacomp_apply")
+    return state

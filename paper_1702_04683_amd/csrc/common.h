@@ -1,0 +1,41 @@
+// Shared host/device helpers of the HIP library (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adacomp.h"
+
+namespace adacomp {
+
+constexpr int WAVE = 64;
+constexpr uint32_t KEY_MASK = 0x7fffffffu;
+
+// Magnitude key: IEEE-754 bit pattern with the sign cleared.  Unsigned order of
+// the key is the order of |x| ("largest ... in absolute value", Alg. 1,
+// SELECT_GRAD); denormals keep their exact order, +-0 map to 0.
+__device__ __forceinline__ uint32_t mag_key(uint32_t bits) { return bits & KEY_MASK; }
+
+// Number of set bits of `m` below the calling lane (wave64).
+__device__ __forceinline__ uint32_t lanes_below(uint64_t m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+__device__ __forceinline__ uint32_t popc64(uint64_t m) { return (uint32_t)__popcll(m); }
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Asynchronous host->device upload of small tables through kernel arguments.
+// The payload travels inside the launch packet, so the host buffer may be freed
+// as soon as the call returns, no pinned memory is needed and the copy can be
+// captured into a graph like any other kernel.
+constexpr uint32_t PUT_WORDS = 448;  // 3584 bytes of payload per launch
+struct PutPayload {
+    uint64_t w[PUT_WORDS];
+};
+hipError_t put_async(void *dst_dev, const void *src_host, size_t bytes, hipStream_t s);
+
+// dst[i] = value for i < n (32-bit words)
+hipError_t fill_u32_async(uint32_t *dst_dev, uint32_t value, size_t n, hipStream_t s);
+
+}  // namespace adacomp

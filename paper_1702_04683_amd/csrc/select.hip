@@ -1,0 +1,833 @@
+// adacomp_select: SELECT_GRAD of Alg. 1 on gfx950.
+//
+// Exact per-tensor top-k by magnitude, output in ascending index order, ties at the
+// threshold broken towards the lower index.  Everything is integer work on the
+// magnitude key (sign-cleared IEEE bits); no floating-point comparison is made.
+//
+// Pipeline (all tensors of the update go through each launch together):
+//   1. sample histogram   a strided sample of 1 KB pieces of every tensor is binned on
+//                         the top 12 key bits (LDS histogram per workgroup);
+//   2. pick               from it a conservative filter threshold t_lo is chosen so that
+//                         #{key >= t_lo} >= k with overwhelming probability and not
+//                         much more (exactly, when the sample is the whole tensor);
+//   3. filter             the one full streaming read: every wave owns a contiguous
+//                         8192-element segment and compacts, in index order, the
+//                         entries with key >= t_lo into its own candidate region;
+//   4. check              a tensor whose candidates are fewer than k or overflowed a
+//                         region is switched to the dense source (always exact);
+//   5. radix descent      12 + 12 + 7 bit histograms over the candidates (or the dense
+//                         tensor) give the exact threshold key T and the tie quota r;
+//   6. count / scan / emit  per-segment counts of key > T and key == T, their
+//                         exclusive scans, and the order-preserving write of exactly k
+//                         (index, value) pairs.
+// Tensors with k == n are copied (identity), tensors with k == 0 produce nothing,
+// tensors with k > n/8 skip steps 1-4.
+#include <algorithm>
+#include <cstring>
+#include <cmath>
+#include <vector>
+
+#include "common.h"
+
+namespace adacomp {
+namespace {
+
+constexpr uint32_t WSEG = 8192;     // elements per wave segment
+constexpr uint32_t ROUND = 1024;    // elements per wave iteration: 4 x (64 lanes x float4)
+constexpr uint32_t PIECE = 256;     // elements per wave-wide float4 load
+constexpr uint32_t BINS = 4096;     // histogram bins (12 key bits)
+constexpr uint32_t HSEGS = 64;      // segments per histogram workgroup
+constexpr uint32_t SPIECES = 64;    // sampled pieces per sample-histogram workgroup
+constexpr uint32_t BLOCK = 256;     // threads per workgroup = 4 waves
+constexpr uint32_t WAVES = BLOCK / WAVE;
+constexpr uint32_t IDENT_TILE = BLOCK * 16;  // elements per identity-copy workgroup
+
+enum : uint32_t { MODE_EMPTY = 0, MODE_IDENTITY = 1, MODE_FILTER = 2, MODE_DENSE = 3 };
+
+struct LayerDesc {
+    const float *g;
+    uint64_t out_off;    // first output entry of this tensor (layer_off[l])
+    uint64_t cand_base;  // first candidate slot of this tensor
+    uint32_t n, k;
+    uint32_t mode;
+    uint32_t vec;        // data pointer is 16-byte aligned
+    uint32_t nseg;       // wave segments taking part in filter / descent / emit
+    uint32_t seg_base;   // first global segment id
+    uint32_t cap;        // candidate slots per segment
+    uint32_t stride;     // one piece sampled out of `stride`
+    uint32_t npieces;    // pieces in the tensor
+    uint32_t npieces_s;  // sampled pieces
+    uint32_t target;     // sample count the filter threshold must cover
+    uint32_t sblk_base;  // prefix sums of workgroup counts, one per kernel shape
+    uint32_t wblk_base;  //   one segment per wave
+    uint32_t hblk_base;  //   HSEGS segments per workgroup
+    uint32_t iblk_base;  //   identity copy
+    uint32_t pad;
+};
+static_assert(sizeof(LayerDesc) % 8 == 0, "descriptor table is uploaded as 64-bit words");
+
+struct LayerState {
+    uint32_t t_lo;       // candidates are the entries with key >= t_lo
+    uint32_t use_dense;  // descent and emit read the tensor itself, not the candidates
+    uint32_t prefix;     // key bits fixed so far by the radix descent
+    uint32_t k_rem;      // rank still to resolve inside the prefix
+    uint32_t T;          // threshold key
+    uint32_t r;          // number of entries with key == T to keep (lowest indices)
+    uint32_t pad[2];
+};
+
+struct Workspace {
+    LayerDesc *desc;      // [L+1]
+    LayerState *state;    // [L]
+    uint32_t *hist;       // [L][BINS]
+    uint32_t *seg_cnt;    // [nseg_total] candidates found per segment
+    uint32_t *seg_gt;     // [nseg_total] #key > T, then exclusive prefix within the tensor
+    uint32_t *seg_eq;     // [nseg_total] #key == T, then exclusive prefix within the tensor
+    uint32_t *cand_idx;   // [cand_total]
+    uint32_t *cand_val;   // [cand_total] raw value bits
+    size_t bytes;
+};
+
+struct Plan {
+    std::vector<LayerDesc> desc;  // L+1, the last one carries the totals
+    uint64_t nseg_total = 0, cand_total = 0, out_total = 0;
+};
+
+uint32_t sample_piece(uint32_t p, uint32_t stride, uint32_t npieces) {
+    uint32_t j = ((p * 2654435761u) >> 16) & (stride - 1);
+    uint64_t q = (uint64_t)p * stride + j;
+    return q < npieces ? (uint32_t)q : npieces - 1;
+}
+
+int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double rate,
+              const uint64_t *k_override, Plan &plan) {
+    if (!(rate >= 0.0 && rate <= 1.0)) return ADACOMP_ERR_RATE;
+    plan.desc.assign((size_t)L + 1, LayerDesc{});
+    uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, hblk = 0, iblk = 0;
+    for (uint32_t l = 0; l < L; ++l) {
+        if (n[l] > 0xffffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
+        uint64_t k64 = k_override ? k_override[l] : adacomp_count(n[l], rate);
+        if (k64 > n[l]) return ADACOMP_ERR_K_RANGE;
+        LayerDesc &d = plan.desc[l];
+        d.g = data ? data[l] : nullptr;
+        d.n = (uint32_t)n[l];
+        d.k = (uint32_t)k64;
+        d.vec = data ? (((uintptr_t)data[l] & 15u) == 0) : 1;
+        d.out_off = out;
+        d.cand_base = cand;
+        d.seg_base = (uint32_t)seg;
+        d.sblk_base = (uint32_t)sblk;
+        d.wblk_base = (uint32_t)wblk;
+        d.hblk_base = (uint32_t)hblk;
+        d.iblk_base = (uint32_t)iblk;
+        d.npieces = (uint32_t)((n[l] + PIECE - 1) / PIECE);
+        d.stride = 1;
+        if (d.n == 0 || d.k == 0) {
+            d.mode = MODE_EMPTY;
+        } else if (d.k == d.n) {
+            d.mode = MODE_IDENTITY;
+            iblk += (n[l] + IDENT_TILE - 1) / IDENT_TILE;
+        } else {
+            d.nseg = (uint32_t)((n[l] + WSEG - 1) / WSEG);
+            d.mode = (8ull * d.k > d.n) ? MODE_DENSE : MODE_FILTER;
+            if (d.mode == MODE_FILTER) {
+                // sample about 128K elements or more, at most one piece in 64
+                uint32_t stride = 64;
+                while (stride > 1 && d.npieces / stride < 512) stride >>= 1;
+                double m_est = 0;
+                for (;; stride >>= 1) {
+                    d.stride = stride;
+                    d.npieces_s = (d.npieces + stride - 1) / stride;
+                    if (stride == 1) {
+                        d.target = d.k;
+                        m_est = (double)d.k * 1.5;
+                        break;
+                    }
+                    // exact number of sampled elements: only the last piece can be short
+                    uint64_t ns = (uint64_t)d.npieces_s * PIECE;
+                    if (sample_piece(d.npieces_s - 1, stride, d.npieces) == d.npieces - 1)
+                        ns -= (uint64_t)d.npieces * PIECE - n[l];
+                    double f = (double)ns / (double)n[l];
+                    double kf = (double)d.k * f;
+                    double tgt = std::ceil(kf + 6.0 * std::sqrt(kf) + 8.0);
+                    m_est = 1.5 * tgt / f;
+                    if (m_est <= (double)n[l] / 4.0) {
+                        d.target = (uint32_t)tgt;
+                        break;
+                    }
+                }
+                double per_seg = m_est * (double)WSEG / (double)n[l];
+                uint64_t cap = (uint64_t)std::ceil(3.0 * per_seg) + 64;
+                d.cap = (uint32_t)std::min<uint64_t>(cap, WSEG);
+                cand += (uint64_t)d.nseg * d.cap;
+                sblk += (d.npieces_s + SPIECES - 1) / SPIECES;
+            }
+            seg += d.nseg;
+            wblk += (d.nseg + WAVES - 1) / WAVES;
+            hblk += (d.nseg + HSEGS - 1) / HSEGS;
+        }
+        out += d.k;
+    }
+    if (seg > 0xffffffffull || sblk > 0x7fffffffull || wblk > 0x7fffffffull ||
+        hblk > 0x7fffffffull || iblk > 0x7fffffffull)
+        return ADACOMP_ERR_LAYER_TOO_LARGE;
+    LayerDesc &e = plan.desc[L];
+    e.out_off = out;
+    e.cand_base = cand;
+    e.seg_base = (uint32_t)seg;
+    e.sblk_base = (uint32_t)sblk;
+    e.wblk_base = (uint32_t)wblk;
+    e.hblk_base = (uint32_t)hblk;
+    e.iblk_base = (uint32_t)iblk;
+    plan.nseg_total = seg;
+    plan.cand_total = cand;
+    plan.out_total = out;
+    return ADACOMP_OK;
+}
+
+void carve(const Plan &plan, uint32_t L, void *base, Workspace &ws) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        void *p = base ? (char *)base + off : nullptr;
+        off += align_up(bytes ? bytes : 1, 256);
+        return p;
+    };
+    ws.desc = (LayerDesc *)take(((size_t)L + 1) * sizeof(LayerDesc));
+    ws.state = (LayerState *)take((size_t)L * sizeof(LayerState));
+    ws.hist = (uint32_t *)take((size_t)L * BINS * sizeof(uint32_t));
+    ws.seg_cnt = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
+    ws.seg_gt = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
+    ws.seg_eq = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
+    ws.cand_idx = (uint32_t *)take(plan.cand_total * sizeof(uint32_t));
+    ws.cand_val = (uint32_t *)take(plan.cand_total * sizeof(uint32_t));
+    ws.bytes = off;
+}
+
+// ------------------------------------------------------------------ device side
+
+template <uint32_t LayerDesc::*BASE>
+__device__ __forceinline__ uint32_t find_layer(const LayerDesc *d, uint32_t L, uint32_t blk) {
+    uint32_t lo = 0, hi = L;  // the last l with d[l].*BASE <= blk owns workgroup blk
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (d[mid].*BASE <= blk) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Four consecutive elements starting at `base`; elements at or beyond `lim` read as 0.
+__device__ __forceinline__ uint4 load4(const float *g, uint32_t base, uint32_t lim, bool vec) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (base >= lim) return v;
+    const uint32_t *p = reinterpret_cast<const uint32_t *>(g) + base;
+    if (vec && lim - base >= 4) return *reinterpret_cast<const uint4 *>(p);
+    v.x = p[0];
+    if (lim - base > 1) v.y = p[1];
+    if (lim - base > 2) v.z = p[2];
+    if (lim - base > 3) v.w = p[3];
+    return v;
+}
+
+// Visit the elements [lo, hi) of a tensor with one wave, in index order: the visitor
+// is called wave-wide once per 256-element piece with each lane holding 4 consecutive
+// elements (idx[c] = first + c, bits[c]); nvalid of them are inside the range.
+template <class F>
+__device__ __forceinline__ void visit_dense(const float *g, bool vec, uint32_t lo, uint32_t hi, F &&f) {
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
+    for (uint32_t r = lo; r < hi; r += ROUND) {
+        uint4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = load4(g, r + j * PIECE + lane * 4, hi, vec);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t first = r + j * PIECE + lane * 4;
+            if (r + j * PIECE >= hi) break;  // wave-uniform
+            const uint32_t idx[4] = {first, first + 1, first + 2, first + 3};
+            const uint32_t bits[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+            const uint32_t nvalid = first >= hi ? 0u : (hi - first < 4u ? hi - first : 4u);
+            f(idx, bits, nvalid);
+        }
+    }
+}
+
+// Visit the candidates of one segment with one wave, in index order, one per lane.
+template <class F>
+__device__ __forceinline__ void visit_cand(const uint32_t *cidx, const uint32_t *cval, uint32_t count, F &&f) {
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
+    for (uint32_t e0 = 0; e0 < count; e0 += WAVE) {
+        const uint32_t e = e0 + lane;
+        const uint32_t ok = e < count;
+        const uint32_t idx[1] = {ok ? cidx[e] : 0u};
+        const uint32_t bits[1] = {ok ? cval[e] : 0u};
+        f(idx, bits, ok);
+    }
+}
+
+// Visit segment `seg` of tensor d from whichever source the tensor currently uses.
+template <class F>
+__device__ __forceinline__ void visit_segment(const LayerDesc &d, const LayerState &st, const Workspace &ws,
+                                              uint32_t seg, F &&f) {
+    if (st.use_dense) {
+        const uint32_t lo = seg * WSEG;
+        const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
+        visit_dense(d.g, d.vec != 0, lo, hi, f);
+    } else {
+        const uint64_t base = d.cand_base + (uint64_t)seg * d.cap;
+        const uint32_t c = ws.seg_cnt[d.seg_base + seg];
+        visit_cand(ws.cand_idx + base, ws.cand_val + base, c < d.cap ? c : d.cap, f);
+    }
+}
+
+// Workgroup-wide: the largest bin b of h[0..nbins) whose suffix sum (bins >= b) reaches
+// `target`, and the sum `above` of the bins > b.  If even the total falls short, b = 0.
+// nbins <= BINS, BLOCK threads, 16 consecutive bins per thread.  All threads return
+// the same pair.
+__device__ void find_bin_from_top(const uint32_t *h, uint32_t nbins, uint32_t target,
+                                  uint32_t &bin, uint32_t &above) {
+    __shared__ uint32_t s_suffix[BLOCK + 1];
+    __shared__ uint32_t s_bin, s_above;
+    const uint32_t t = threadIdx.x;
+    uint32_t c[16];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+        const uint32_t i = t * 16 + b;
+        c[b] = i < nbins ? h[i] : 0u;
+        sum += c[b];
+    }
+    if (t == 0) {
+        s_bin = 0;
+        s_above = 0;
+        s_suffix[BLOCK] = 0;
+    }
+    s_suffix[t] = sum;
+    __syncthreads();
+    for (uint32_t step = 1; step < BLOCK; step <<= 1) {  // inclusive suffix scan
+        const uint32_t add = t + step < BLOCK ? s_suffix[t + step] : 0u;
+        __syncthreads();
+        s_suffix[t] += add;
+        __syncthreads();
+    }
+    const uint32_t incl = s_suffix[t], excl = s_suffix[t + 1];
+    if (excl < target && target <= incl) {
+        uint32_t acc = excl;
+        for (int b = 15; b >= 0; --b) {
+            if (acc + c[b] >= target) {
+                s_bin = t * 16 + b;
+                s_above = acc;
+                break;
+            }
+            acc += c[b];
+        }
+    }
+    if (t == 0 && incl < target) s_above = incl - c[0];
+    __syncthreads();
+    bin = s_bin;
+    above = s_above;
+    __syncthreads();
+}
+
+// LDS histogram helpers ---------------------------------------------------------
+__device__ __forceinline__ void lds_hist_clear(uint32_t *h) {
+    for (uint32_t i = threadIdx.x; i < BINS; i += BLOCK) h[i] = 0;
+    __syncthreads();
+}
+
+__device__ __forceinline__ void lds_hist_flush(const uint32_t *h, uint32_t *global_hist, uint32_t nbins) {
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nbins; i += BLOCK) {
+        const uint32_t c = h[i];
+        if (c) atomicAdd(global_hist + i, c);
+    }
+}
+
+// Add one matching element per (lane, component) to an LDS histogram.  Zero keys, which
+// can be half of a tensor, are counted with a ballot instead of 64 colliding atomics.
+template <int NC>
+__device__ __forceinline__ void lds_hist_add(uint32_t *h, const uint32_t (&key)[NC], const bool (&match)[NC],
+                                             const uint32_t (&bin)[NC], uint32_t &zero_run) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const bool z = match[c] && key[c] == 0;
+        zero_run += popc64(__ballot(z));
+        if (match[c] && !z) atomicAdd(&h[bin[c]], 1u);
+    }
+}
+
+// ---- step 1: sample histogram on the top 12 key bits -----------------------------
+__global__ __launch_bounds__(BLOCK) void k_sample_hist(Workspace ws, uint32_t L) {
+    __shared__ uint32_t h[BINS];
+    const uint32_t l = find_layer<&LayerDesc::sblk_base>(ws.desc, L, blockIdx.x);
+    const LayerDesc d = ws.desc[l];
+    const uint32_t b = blockIdx.x - d.sblk_base;
+    const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+    lds_hist_clear(h);
+    const uint32_t p_lo = b * SPIECES;
+    const uint32_t p_hi = p_lo + SPIECES < d.npieces_s ? p_lo + SPIECES : d.npieces_s;
+    uint32_t zero_run = 0;
+    for (uint32_t p0 = p_lo + wave * 4; p0 < p_hi; p0 += WAVES * 4) {
+        uint4 v[4];
+        uint32_t first[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t p = p0 + j;
+            uint32_t piece = 0;
+            if (p < p_hi) {
+                const uint32_t jit = ((p * 2654435761u) >> 16) & (d.stride - 1);
+                const uint64_t q = (uint64_t)p * d.stride + jit;
+                piece = q < d.npieces ? (uint32_t)q : d.npieces - 1;
+            }
+            first[j] = piece * PIECE + lane * 4;
+            v[j] = load4(d.g, first[j], p < p_hi ? d.n : 0u, d.vec != 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (p0 + j >= p_hi) break;
+            const uint32_t nvalid = first[j] >= d.n ? 0u : (d.n - first[j] < 4u ? d.n - first[j] : 4u);
+            const uint32_t bits[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+            uint32_t key[4], bin[4];
+            bool match[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                key[c] = mag_key(bits[c]);
+                bin[c] = key[c] >> 19;
+                match[c] = (uint32_t)c < nvalid;
+            }
+            lds_hist_add<4>(h, key, match, bin, zero_run);
+        }
+    }
+    if (lane == 0 && zero_run) atomicAdd(&h[0], zero_run);
+    lds_hist_flush(h, ws.hist + (size_t)l * BINS, BINS);
+}
+
+// ---- step 2: initialise per-tensor state, choose the filter threshold -----------
+__global__ __launch_bounds__(BLOCK) void k_pick(Workspace ws) {
+    const uint32_t l = blockIdx.x;
+    const LayerDesc d = ws.desc[l];
+    uint32_t *h = ws.hist + (size_t)l * BINS;
+    uint32_t t_lo = 0;
+    if (d.mode == MODE_FILTER) {
+        uint32_t bin, above;
+        find_bin_from_top(h, BINS, d.target, bin, above);
+        t_lo = bin << 19;
+        for (uint32_t i = threadIdx.x; i < BINS; i += BLOCK) h[i] = 0;
+    }
+    if (threadIdx.x == 0) {
+        LayerState st;
+        st.t_lo = t_lo;
+        st.use_dense = d.mode == MODE_DENSE;
+        st.prefix = 0;
+        st.k_rem = d.k;
+        st.T = 0;
+        st.r = 0;
+        st.pad[0] = st.pad[1] = 0;
+        ws.state[l] = st;
+    }
+}
+
+// ---- step 3: the streaming read; ordered compaction of key >= t_lo per wave ------
+__global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L) {
+    const uint32_t l = find_layer<&LayerDesc::wblk_base>(ws.desc, L, blockIdx.x);
+    const LayerDesc d = ws.desc[l];
+    if (d.mode != MODE_FILTER) return;
+    const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+    const uint32_t seg = (blockIdx.x - d.wblk_base) * WAVES + wave;
+    if (seg >= d.nseg) return;
+    const uint32_t t_lo = ws.state[l].t_lo;
+    const uint64_t base = d.cand_base + (uint64_t)seg * d.cap;
+    uint32_t *cidx = ws.cand_idx + base;
+    uint32_t *cval = ws.cand_val + base;
+    const uint32_t cap = d.cap;
+    const uint32_t lo = seg * WSEG;
+    const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
+    uint32_t run = 0;  // candidates found so far in this segment (wave-uniform)
+    visit_dense(d.g, d.vec != 0, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+        bool f[4];
+        uint64_t m[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            f[c] = (uint32_t)c < nvalid && mag_key(bits[c]) >= t_lo;
+            m[c] = __ballot(f[c]);
+        }
+        if ((m[0] | m[1] | m[2] | m[3]) == 0) return;
+        uint32_t pos = run + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (f[c]) {
+                if (pos < cap) {
+                    cidx[pos] = idx[c];
+                    cval[pos] = bits[c];
+                }
+                ++pos;
+            }
+        }
+        run += popc64(m[0]) + popc64(m[1]) + popc64(m[2]) + popc64(m[3]);
+    });
+    if (lane == 0) ws.seg_cnt[d.seg_base + seg] = run;
+}
+
+// ---- step 4: enough candidates, and none lost? -----------------------------------
+__global__ __launch_bounds__(BLOCK) void k_check(Workspace ws) {
+    __shared__ unsigned long long s_total;
+    __shared__ uint32_t s_over;
+    const uint32_t l = blockIdx.x;
+    const LayerDesc d = ws.desc[l];
+    if (d.mode != MODE_FILTER) return;
+    if (threadIdx.x == 0) {
+        s_total = 0;
+        s_over = 0;
+    }
+    __syncthreads();
+    unsigned long long total = 0;
+    uint32_t over = 0;
+    for (uint32_t s = threadIdx.x; s < d.nseg; s += BLOCK) {
+        const uint32_t c = ws.seg_cnt[d.seg_base + s];
+        total += c;
+        over |= c > d.cap;
+    }
+    atomicAdd(&s_total, total);
+    if (over) atomicOr(&s_over, 1u);
+    __syncthreads();
+    if (threadIdx.x == 0 && (s_over || s_total < d.k)) ws.state[l].use_dense = 1;
+}
+
+// ---- step 5: radix descent, one histogram + one resolve per level ----------------
+// level 0: bins = key[30:19]; level 1: key[30:19] == prefix, bins = key[18:7];
+// level 2: key[30:7] == prefix, bins = key[6:0].
+template <int LEVEL>
+__global__ __launch_bounds__(BLOCK) void k_hist(Workspace ws, uint32_t L) {
+    __shared__ uint32_t h[BINS];
+    const uint32_t l = find_layer<&LayerDesc::hblk_base>(ws.desc, L, blockIdx.x);
+    const LayerDesc d = ws.desc[l];
+    const LayerState st = ws.state[l];
+    const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+    const uint32_t s_lo = (blockIdx.x - d.hblk_base) * HSEGS;
+    const uint32_t s_hi = s_lo + HSEGS < d.nseg ? s_lo + HSEGS : d.nseg;
+    lds_hist_clear(h);
+    uint32_t zero_run = 0;
+    const uint32_t prefix = st.prefix;
+    for (uint32_t seg = s_lo + wave; seg < s_hi; seg += WAVES) {
+        visit_segment(d, st, ws, seg, [&](const auto &idx, const auto &bits, uint32_t nvalid) {
+            constexpr int NC = sizeof(bits) / sizeof(bits[0]);
+            uint32_t key[NC], bin[NC];
+            bool match[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                key[c] = mag_key(bits[c]);
+                match[c] = (uint32_t)c < nvalid;
+                if (LEVEL == 0) {
+                    bin[c] = key[c] >> 19;
+                } else if (LEVEL == 1) {
+                    match[c] = match[c] && (key[c] >> 19) == prefix;
+                    bin[c] = (key[c] >> 7) & 0xfffu;
+                } else {
+                    match[c] = match[c] && (key[c] >> 7) == prefix;
+                    bin[c] = key[c] & 0x7fu;
+                }
+            }
+            (void)idx;
+            lds_hist_add<NC>(h, key, match, bin, zero_run);
+        });
+    }
+    if (lane == 0 && zero_run) atomicAdd(&h[0], zero_run);
+    lds_hist_flush(h, ws.hist + (size_t)l * BINS, LEVEL == 2 ? 128u : BINS);
+}
+
+template <int LEVEL>
+__global__ __launch_bounds__(BLOCK) void k_resolve(Workspace ws) {
+    const uint32_t l = blockIdx.x;
+    const LayerDesc d = ws.desc[l];
+    if (d.nseg == 0) return;
+    uint32_t *h = ws.hist + (size_t)l * BINS;
+    const LayerState st = ws.state[l];
+    constexpr uint32_t nbins = LEVEL == 2 ? 128u : BINS;
+    uint32_t bin, above;
+    find_bin_from_top(h, nbins, st.k_rem, bin, above);
+    for (uint32_t i = threadIdx.x; i < nbins; i += BLOCK) h[i] = 0;
+    if (threadIdx.x == 0) {
+        const uint32_t prefix = (st.prefix << (LEVEL == 2 ? 7 : 12)) | bin;
+        const uint32_t k_rem = st.k_rem - above;
+        ws.state[l].prefix = prefix;
+        ws.state[l].k_rem = k_rem;
+        if (LEVEL == 2) {
+            ws.state[l].T = prefix;
+            ws.state[l].r = k_rem;
+        }
+    }
+}
+
+// ---- step 6: per-segment counts, scans, ordered emit ------------------------------
+__global__ __launch_bounds__(BLOCK) void k_count(Workspace ws, uint32_t L) {
+    const uint32_t l = find_layer<&LayerDesc::wblk_base>(ws.desc, L, blockIdx.x);
+    const LayerDesc d = ws.desc[l];
+    const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+    const uint32_t seg = (blockIdx.x - d.wblk_base) * WAVES + wave;
+    if (seg >= d.nseg) return;
+    const LayerState st = ws.state[l];
+    const uint32_t T = st.T;
+    uint32_t gt = 0, eq = 0;
+    visit_segment(d, st, ws, seg, [&](const auto &idx, const auto &bits, uint32_t nvalid) {
+        constexpr int NC = sizeof(bits) / sizeof(bits[0]);
+        (void)idx;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const uint32_t key = mag_key(bits[c]);
+            const bool ok = (uint32_t)c < nvalid;
+            gt += popc64(__ballot(ok && key > T));
+            eq += popc64(__ballot(ok && key == T));
+        }
+    });
+    if (lane == 0) {
+        ws.seg_gt[d.seg_base + seg] = gt;
+        ws.seg_eq[d.seg_base + seg] = eq;
+    }
+}
+
+// Exclusive scan over the segments of one tensor of both count arrays, in place.
+__global__ __launch_bounds__(BLOCK) void k_scan(Workspace ws) {
+    __shared__ uint32_t s_a[BLOCK], s_b[BLOCK];
+    const uint32_t l = blockIdx.x;
+    const LayerDesc d = ws.desc[l];
+    if (d.nseg == 0) return;
+    uint32_t *gt = ws.seg_gt + d.seg_base, *eq = ws.seg_eq + d.seg_base;
+    const uint32_t t = threadIdx.x;
+    uint32_t carry_a = 0, carry_b = 0;
+    for (uint32_t s0 = 0; s0 < d.nseg; s0 += BLOCK) {
+        const uint32_t s = s0 + t;
+        const uint32_t a = s < d.nseg ? gt[s] : 0u, b = s < d.nseg ? eq[s] : 0u;
+        s_a[t] = a;
+        s_b[t] = b;
+        __syncthreads();
+        for (uint32_t step = 1; step < BLOCK; step <<= 1) {  // inclusive prefix scan
+            const uint32_t xa = t >= step ? s_a[t - step] : 0u, xb = t >= step ? s_b[t - step] : 0u;
+            __syncthreads();
+            s_a[t] += xa;
+            s_b[t] += xb;
+            __syncthreads();
+        }
+        if (s < d.nseg) {
+            gt[s] = carry_a + s_a[t] - a;
+            eq[s] = carry_b + s_b[t] - b;
+        }
+        carry_a += s_a[BLOCK - 1];
+        carry_b += s_b[BLOCK - 1];
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(BLOCK) void k_emit(Workspace ws, uint32_t L, uint32_t *out_idx, uint32_t *out_val) {
+    const uint32_t l = find_layer<&LayerDesc::wblk_base>(ws.desc, L, blockIdx.x);
+    const LayerDesc d = ws.desc[l];
+    const uint32_t wave = threadIdx.x / WAVE;
+    const uint32_t seg = (blockIdx.x - d.wblk_base) * WAVES + wave;
+    if (seg >= d.nseg) return;
+    const LayerState st = ws.state[l];
+    const uint32_t T = st.T, r = st.r;
+    uint32_t run_gt = ws.seg_gt[d.seg_base + seg];  // entries with key > T before this segment
+    uint32_t run_eq = ws.seg_eq[d.seg_base + seg];  // entries with key == T before this segment
+    uint32_t *oi = out_idx + d.out_off;
+    uint32_t *ov = out_val + d.out_off;
+    visit_segment(d, st, ws, seg, [&](const auto &idx, const auto &bits, uint32_t nvalid) {
+        constexpr int NC = sizeof(bits) / sizeof(bits[0]);
+        bool g[NC], e[NC];
+        uint64_t mg[NC], me[NC];
+        uint64_t any = 0;
+        uint32_t gt_b = run_gt, eq_b = run_eq, tot_g = 0, tot_e = 0;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const uint32_t key = mag_key(bits[c]);
+            const bool ok = (uint32_t)c < nvalid;
+            g[c] = ok && key > T;
+            e[c] = ok && key == T;
+            mg[c] = __ballot(g[c]);
+            me[c] = __ballot(e[c]);
+            any |= mg[c] | me[c];
+            gt_b += lanes_below(mg[c]);
+            eq_b += lanes_below(me[c]);
+            tot_g += popc64(mg[c]);
+            tot_e += popc64(me[c]);
+        }
+        if (any == 0) return;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if (g[c]) {
+                const uint32_t pos = gt_b + (eq_b < r ? eq_b : r);
+                oi[pos] = idx[c];
+                ov[pos] = bits[c];
+                ++gt_b;
+            } else if (e[c]) {
+                if (eq_b < r) {
+                    const uint32_t pos = gt_b + eq_b;
+                    oi[pos] = idx[c];
+                    ov[pos] = bits[c];
+                }
+                ++eq_b;
+            }
+        }
+        run_gt += tot_g;
+        run_eq += tot_e;
+    });
+}
+
+// ---- k == n: the update is the tensor itself --------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_identity(Workspace ws, uint32_t L, uint32_t *out_idx, uint32_t *out_val) {
+    const uint32_t l = find_layer<&LayerDesc::iblk_base>(ws.desc, L, blockIdx.x);
+    const LayerDesc d = ws.desc[l];
+    const uint32_t lo = (blockIdx.x - d.iblk_base) * IDENT_TILE;
+    const uint32_t hi = d.n - lo < IDENT_TILE ? d.n : lo + IDENT_TILE;
+    const uint32_t *g = reinterpret_cast<const uint32_t *>(d.g);
+    for (uint32_t i = lo + threadIdx.x; i < hi; i += BLOCK) {
+        out_idx[d.out_off + i] = i;
+        out_val[d.out_off + i] = g[i];
+    }
+}
+
+__global__ void k_put(uint64_t *dst, PutPayload a, uint32_t nwords) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nwords) dst[i] = a.w[i];
+}
+
+__global__ void k_fill(uint32_t *dst, uint32_t value, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) dst[i] = value;
+}
+
+}  // namespace
+
+hipError_t put_async(void *dst_dev, const void *src_host, size_t bytes, hipStream_t s) {
+    const size_t words = (bytes + 7) / 8;
+    const char *src = static_cast<const char *>(src_host);
+    for (size_t w0 = 0; w0 < words; w0 += PUT_WORDS) {
+        PutPayload a;
+        const size_t nw = std::min<size_t>(PUT_WORDS, words - w0);
+        const size_t nb = std::min<size_t>(nw * 8, bytes - w0 * 8);
+        a.w[nw - 1] = 0;
+        std::memcpy(a.w, src + w0 * 8, nb);
+        hipLaunchKernelGGL(k_put, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s,
+                           static_cast<uint64_t *>(dst_dev) + w0, a, (uint32_t)nw);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t fill_u32_async(uint32_t *dst_dev, uint32_t value, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 1023) / 1024, 4096);
+    hipLaunchKernelGGL(k_fill, dim3(blocks), dim3(256), 0, s, dst_dev, value, n);
+    return hipGetLastError();
+}
+
+}  // namespace adacomp
+
+using namespace adacomp;
+
+extern "C" uint64_t adacomp_count(uint64_t n, double rate) {
+    if (n == 0 || !(rate > 0.0) || rate > 1.0) return 0;
+    if (rate == 1.0) return n;
+    const double scaled = rate * (double)n;
+    const double guarded = scaled * (1.0 - 0x1p-40);
+    double k = std::ceil(guarded);
+    if (k < 1.0) k = 1.0;
+    if (k > (double)n) return n;
+    return (uint64_t)k;
+}
+
+extern "C" int adacomp_select_workspace(const uint64_t *n, uint32_t L, double rate,
+                                        const uint64_t *k_override, size_t *bytes) {
+    if (!bytes || (L && !n)) return ADACOMP_ERR_NULL;
+    Plan plan;
+    int rc = make_plan(n, nullptr, L, rate, k_override, plan);
+    if (rc) return rc;
+    Workspace ws;
+    carve(plan, L, nullptr, ws);
+    *bytes = ws.bytes;
+    return ADACOMP_OK;
+}
+
+#define LAUNCH(kernel, grid, ...)                                                   \
+    do {                                                                            \
+        if ((grid) > 0) {                                                           \
+            hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(BLOCK), 0, s, __VA_ARGS__); \
+            if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;            \
+        }                                                                           \
+    } while (0)
+
+extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double rate,
+                              const uint64_t *k_override, adacomp_update_t *out,
+                              void *workspace, size_t ws_bytes, void *hip_stream) {
+    if (!out || (L && !layers) || !out->layer_off || !out->layer_off_dev) return ADACOMP_ERR_NULL;
+    if (out->num_layers != L) return ADACOMP_ERR_LAYER_MISMATCH;
+    std::vector<uint64_t> n(L);
+    std::vector<const float *> data(L);
+    for (uint32_t l = 0; l < L; ++l) {
+        n[l] = layers[l].n;
+        data[l] = layers[l].data;
+        if (n[l] && !data[l]) return ADACOMP_ERR_NULL;
+        if ((uintptr_t)data[l] & 3u) return ADACOMP_ERR_ALIGNMENT;
+    }
+    Plan plan;
+    int rc = make_plan(n.data(), data.data(), L, rate, k_override, plan);
+    if (rc) return rc;
+    if (plan.out_total > out->cap) return ADACOMP_ERR_CAPACITY;
+    if (plan.out_total && (!out->idx || !out->val)) return ADACOMP_ERR_NULL;
+    if (((uintptr_t)out->idx & 3u) || ((uintptr_t)out->val & 3u) || ((uintptr_t)out->layer_off_dev & 7u))
+        return ADACOMP_ERR_ALIGNMENT;
+    Workspace ws;
+    carve(plan, L, workspace, ws);
+    if (!workspace || ((uintptr_t)workspace & 255u) || ws_bytes < ws.bytes) return ADACOMP_ERR_WORKSPACE;
+
+    std::vector<uint64_t> off((size_t)L + 1);
+    for (uint32_t l = 0; l <= L; ++l) off[l] = out->layer_off[l] = plan.desc[l].out_off;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (put_async(out->layer_off_dev, off.data(), off.size() * sizeof(uint64_t), s) != hipSuccess)
+        return ADACOMP_ERR_HIP;
+    if (L == 0) return ADACOMP_OK;
+    if (put_async(ws.desc, plan.desc.data(), plan.desc.size() * sizeof(LayerDesc), s) != hipSuccess)
+        return ADACOMP_ERR_HIP;
+    if (fill_u32_async(ws.hist, 0u, (size_t)L * BINS, s) != hipSuccess) return ADACOMP_ERR_HIP;
+
+    const LayerDesc &tot = plan.desc[L];
+    uint32_t *out_idx = out->idx;
+    uint32_t *out_val = reinterpret_cast<uint32_t *>(out->val);
+    LAUNCH(k_sample_hist, tot.sblk_base, ws, L);
+    LAUNCH(k_pick, L, ws);
+    if (tot.sblk_base) {  // at least one tensor goes through the filter
+        LAUNCH(k_filter, tot.wblk_base, ws, L);
+        LAUNCH(k_check, L, ws);
+    }
+    if (tot.seg_base) {
+        LAUNCH(k_hist<0>, tot.hblk_base, ws, L);
+        LAUNCH(k_resolve<0>, L, ws);
+        LAUNCH(k_hist<1>, tot.hblk_base, ws, L);
+        LAUNCH(k_resolve<1>, L, ws);
+        LAUNCH(k_hist<2>, tot.hblk_base, ws, L);
+        LAUNCH(k_resolve<2>, L, ws);
+        LAUNCH(k_count, tot.wblk_base, ws, L);
+        LAUNCH(k_scan, L, ws);
+        LAUNCH(k_emit, tot.wblk_base, ws, L, out_idx, out_val);
+    }
+    LAUNCH(k_identity, tot.iblk_base, ws, L, out_idx, out_val);
+    return ADACOMP_OK;
+}
+
+extern "C" const char *adacomp_strerror(int code) {
+    switch (code) {
+        case ADACOMP_OK: return "success";
+        case ADACOMP_ERR_NULL: return "a required pointer is NULL";
+        case ADACOMP_ERR_RATE: return "rate is NaN or outside [0, 1]";
+        case ADACOMP_ERR_LAYER_TOO_LARGE: return "a tensor has 2^32 or more elements";
+        case ADACOMP_ERR_CAPACITY: return "update buffers are smaller than the selected count";
+        case ADACOMP_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
+        case ADACOMP_ERR_LAYER_MISMATCH: return "tensor count or sizes of update/state differ from the parameters";
+        case ADACOMP_ERR_FUTURE_PULL: return "an update was pulled after the time it is applied";
+        case ADACOMP_ERR_K_RANGE: return "k_override exceeds the tensor size";
+        case ADACOMP_ERR_HISTORY: return "an update was pulled before the first update of this call";
+        case ADACOMP_ERR_LR: return "learning rate is not finite";
+        case ADACOMP_ERR_ALIGNMENT: return "a device pointer is not aligned to its element size";
+        case ADACOMP_ERR_HIP: return "a HIP runtime call failed";
+        default: return "unknown adacomp error code";
+    }
+}

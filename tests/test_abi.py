@@ -1,0 +1,130 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and its
+host-side argument checks answer without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_1702_04683_amd as ac
+from paper_1702_04683_amd import binding, build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if hip_build.is_stale():
+        hip_build.build()
+    return ac.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "adacomp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adacomp_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"adacomp_count", "adacomp_select_workspace", "adacomp_select", "adacomp_apply_workspace",
+            "adacomp_apply", "adacomp_strerror"} <= set(names)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_count_matches_oracle_rule(lib):
+    import json
+    rows = json.load(open(os.path.join(ROOT, "tests", "golden", "count_table.json")))["rows"]
+    for n, c, k in rows:
+        assert ac.adacomp_count(n, c) == k
+    import random
+    rnd = random.Random(3)
+    for _ in range(20000):
+        n = rnd.randrange(0, 1 << 32)
+        c = rnd.choice([rnd.random(), rnd.random() ** 4, 1.0 / max(n, 1), 0.0, 1.0, 0.01, 0.005])
+        assert ac.adacomp_count(n, c) == oracle.count(n, c), (n, c)
+
+
+def test_strerror_covers_all_codes(lib):
+    text = open(os.path.join(ROOT, "include", "adacomp.h")).read()
+    codes = [int(v) for v in re.findall(r"ADACOMP_ERR_[A-Z_]+\s*=\s*(-\d+)", text)]
+    assert len(codes) >= 10
+    for c in codes + [0]:
+        assert "unknown" not in ac.adacomp_strerror(c)
+    assert "unknown" in ac.adacomp_strerror(-999)
+
+
+def test_select_workspace_errors(lib):
+    assert ac.adacomp_select_workspace([], 0.5) >= 0
+    assert ac.adacomp_select_workspace([10, 0, 5], 0.5) > 0
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(ac.AdaCompError) as e:
+            ac.adacomp_select_workspace([10], bad)
+        assert e.value.code == -2
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_select_workspace([1 << 32], 0.5)
+    assert e.value.code == -3
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_select_workspace([10], 0.5, k_override=[11])
+    assert e.value.code == -8
+
+
+def test_select_argument_checks_run_before_any_launch(lib):
+    """All of these must fail on the host: there is no GPU here, a launch would not return a code."""
+    n = (C.c_uint64 * 1)(100)
+    off = (C.c_uint64 * 2)()
+    layer = (binding._Layer * 1)()
+    layer[0].data, layer[0].n = 0x1000, 100
+    upd = binding._Update(1, C.cast(off, C.POINTER(C.c_uint64)), 0x2000, 0x3000, 0x4000, 0, 0)
+    call = lambda rate, u, ws, nb: lib.adacomp_select(layer, 1, rate, None, C.byref(u), ws, nb, None)
+    assert call(0.5, upd, 0x10000, 1 << 30) == -4          # capacity 0 < 50
+    upd.cap = 50
+    assert call(2.0, upd, 0x10000, 1 << 30) == -2
+    assert call(0.5, upd, None, 1 << 30) == -5
+    assert call(0.5, upd, 0x10001, 1 << 30) == -5          # misaligned workspace
+    assert call(0.5, upd, 0x10000, 16) == -5               # too small
+    upd.num_layers = 2
+    assert call(0.5, upd, 0x10000, 1 << 30) == -6
+    upd.num_layers = 1
+    layer[0].data = 0x1002
+    assert call(0.5, upd, 0x10000, 1 << 30) == -11
+    layer[0].data = None
+    assert call(0.5, upd, 0x10000, 1 << 30) == -1
+    assert lib.adacomp_select(layer, 1, 0.5, None, None, 0x10000, 1 << 30, None) == -1
+
+
+def test_apply_argument_checks_run_before_any_launch(lib):
+    off = (C.c_uint64 * 2)(0, 3)
+    par = (binding._Layer * 1)()
+    par[0].data, par[0].n = 0x1000, 100
+    cnt = (C.c_void_p * 1)(0x5000)
+    st = binding._State(5, 1, C.cast(cnt, C.POINTER(C.c_void_p)))
+    upd = (binding._Update * 1)()
+    upd[0] = binding._Update(1, C.cast(off, C.POINTER(C.c_uint64)), 0x2000, 0x3000, 0x4000, 3, 5)
+    call = lambda lr=0.1, ws=0x10000, nb=1 << 20: lib.adacomp_apply(par, 1, C.byref(st), upd, 1, lr, ws, nb, None)
+    upd[0].pull_ts = 6
+    assert call() == -7                                     # pulled in the future
+    upd[0].pull_ts = 4
+    assert call() == -9                                     # pulled before this call's first update
+    upd[0].pull_ts = 5
+    assert call(lr=float("inf")) == -10
+    assert call(ws=None) == -5
+    assert call(nb=8) == -5
+    off[1] = 101
+    upd[0].cap = 101
+    assert call() == -6                                     # more entries than the tensor has parameters
+    off[1] = 3
+    upd[0].cap = 2
+    assert call() == -4
+    upd[0].cap = 3
+    upd[0].num_layers = 2
+    assert call() == -6
+    upd[0].num_layers = 1
+    st.num_layers = 2
+    assert call() == -6
+    st.num_layers = 1
+    assert st.t == 5                                        # no failing call advanced the timestamp
+    need = C.c_size_t()
+    assert lib.adacomp_apply_workspace(1, upd, 1, C.byref(need)) == 0 and need.value >= 12

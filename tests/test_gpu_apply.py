@@ -1,0 +1,271 @@
+"""GPU parity: adacomp_apply (HIP, through the C ABI) against the CPU oracle's parameter server.
+
+Contract: parameters within 1e-6 relative of the fp32 oracle (|a-b| <= 1e-6 * max(|a|,|b|,1e-30)).
+Both sides evaluate eqs. 5 and 4 as divide, multiply, subtract in fp32, so in practice the
+results are expected to be identical; the tests report the number of differing entries.
+Against the fp64 oracle the bound is the accumulated fp32 rounding: with m touches of a
+parameter, |err| <= 3 * m * 2^-24 * max|intermediate value|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from helpers import gpu_select, oracle_select_parallel, rel_err, update_to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ac():
+    import paper_1702_04683_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return torch.device("cuda:0")
+
+
+def run_gpu(ac, theta_host, updates_host, pulls, lr, dev, chunks=None, state=None):
+    """updates_host: list of (off, idx, val).  Returns (theta list of numpy, counters, state)."""
+    theta = [torch.from_numpy(t.copy()).to(dev) for t in theta_host]
+    L = len(theta)
+    ups = [ac.Update.from_host(o, i, v, dev, pull_ts=p) for (o, i, v), p in zip(updates_host, pulls)]
+    st = ac.State(theta) if state is None else state
+    chunks = chunks or [len(ups)]
+    pos = 0
+    for c in chunks:
+        part = ups[pos:pos + c]
+        ws = torch.empty(max(ac.adacomp_apply_workspace(L, part), 256), dtype=torch.uint8, device=dev)
+        ac.adacomp_apply(theta, st, part, lr, ws)
+        pos += c
+    torch.cuda.synchronize()
+    return [t.cpu().numpy() for t in theta], [c.cpu().numpy() for c in st.cnt], st
+
+
+def run_oracle(theta_host, updates_host, pulls, lr, method=oracle.HISTORY_LISTS, f64=False):
+    theta = [t.astype(np.float64) if f64 else t.copy() for t in theta_host]
+    ps = oracle.ParameterServer(theta, method, f64=f64)
+    for (o, i, v), p in zip(updates_host, pulls):
+        ps.apply(o, i, v, p, lr)
+    return theta
+
+
+def compare(got, want, what):
+    worst, differing = 0.0, 0
+    for l, (a, b) in enumerate(zip(got, want)):
+        worst = max(worst, rel_err(a, b))
+        differing += int(np.count_nonzero(a.view(np.uint32) != b.view(np.uint32)))
+    print(f"[apply] {what}: max rel err {worst:.3e}, entries not bit-identical: {differing}", flush=True)
+    assert worst <= 1e-6, what
+    return differing
+
+
+def random_updates(rng, sizes, Q, density, pool=None, zero_frac=0.0):
+    ups = []
+    for _ in range(Q):
+        off, idx, val = [0], [], []
+        for n in sizes:
+            k = min(n, max(0, int(round(density * n)))) if n else 0
+            if pool is not None:
+                cand = np.unique(rng.integers(0, min(n, pool), size=k)) if k else np.empty(0, np.int64)
+            else:
+                cand = np.sort(rng.choice(n, size=k, replace=False)) if k else np.empty(0, np.int64)
+            v = rng.standard_normal(cand.size).astype(np.float32)
+            if zero_frac:
+                z = rng.random(cand.size) < zero_frac
+                v[z] = np.where(rng.random(int(z.sum())) < 0.5, 0.0, -0.0).astype(np.float32)
+            idx.append(cand.astype(np.uint32))
+            val.append(v)
+            off.append(off[-1] + cand.size)
+        ups.append((np.array(off, dtype=np.uint64), np.concatenate(idx) if idx else np.empty(0, np.uint32),
+                    np.concatenate(val) if val else np.empty(0, np.float32)))
+    return ups
+
+
+def test_small_random_queues_bit_exact(ac, dev):
+    """Dense overlap, zero-valued entries, empty tensors and empty updates, random pull times."""
+    rng = np.random.default_rng(42)
+    for trial in range(6):
+        sizes = [int(rng.integers(1, 3000)) for _ in range(5)] + [0, 1]
+        Q = int(rng.integers(1, 50))
+        ups = random_updates(rng, sizes, Q, 0.2, zero_frac=0.1)
+        if Q > 3:
+            ups[2] = (np.zeros(len(sizes) + 1, dtype=np.uint64), np.empty(0, np.uint32), np.empty(0, np.float32))
+        pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+        theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+        got, cnt, st = run_gpu(ac, theta0, ups, pulls, 0.05, dev)
+        want = run_oracle(theta0, ups, pulls, 0.05)
+        assert st.t == Q
+        assert compare(got, want, f"random queue {trial}") == 0
+        # the counters are the number of non-zero entries each parameter received
+        for l, n in enumerate(sizes):
+            ref = np.zeros(max(n, 1), dtype=np.int64)
+            for o, i, v in ups:
+                sl = slice(int(o[l]), int(o[l + 1]))
+                np.add.at(ref, i[sl][v[sl] != 0], 1)
+            assert np.array_equal(cnt[l].astype(np.int64), ref)
+
+
+def test_split_calls_equal_one_call_when_pulls_stay_inside(ac, dev):
+    """State carries over between calls (timestamp and counters); a pull before the current call is refused."""
+    rng = np.random.default_rng(8)
+    sizes = [500, 77]
+    Q = 24
+    ups = random_updates(rng, sizes, Q, 0.3)
+    pulls = [max(q - int(rng.integers(0, 4)), (q // 8) * 8) for q in range(Q)]   # never before the chunk start
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    one, _, _ = run_gpu(ac, theta0, ups, pulls, 0.1, dev)
+    three, _, st = run_gpu(ac, theta0, ups, pulls, 0.1, dev, chunks=[8, 8, 8])
+    want = run_oracle(theta0, ups, pulls, 0.1)
+    assert st.t == Q
+    assert compare(one, want, "one call") == 0 and compare(three, want, "three calls") == 0
+    theta = [torch.from_numpy(t.copy()).to(dev) for t in theta0]
+    u = ac.Update.from_host(*ups[0], dev, pull_ts=3)
+    ws = torch.empty(4096, dtype=torch.uint8, device=dev)
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_apply(theta, st, [u], 0.1, ws)
+    assert e.value.code == -9 and st.t == Q
+
+
+def test_closed_forms_on_gpu(ac, dev):
+    """Harmonic sum, the three-worker chronology, unit staleness = plain SGD, keep-all = dense ASGD."""
+    one = (np.array([0, 1], dtype=np.uint64), np.array([0], dtype=np.uint32), np.array([1.0], dtype=np.float32))
+    got, _, _ = run_gpu(ac, [np.zeros(1, np.float32)], [one] * 4, [0] * 4, 1.0, dev)
+    assert abs(float(got[0][0]) + 17 / 6) < 3e-7
+    mk = lambda d: (np.array([0, len(d)], dtype=np.uint64), np.array(sorted(d), dtype=np.uint32),
+                    np.array([d[k] for k in sorted(d)], dtype=np.float32))
+    ups = [mk({0: 1, 1: 1}), mk({1: 1, 2: 1}), mk({1: 1, 2: 1, 3: 1})]
+    got, _, _ = run_gpu(ac, [np.zeros(4, np.float32)], ups, [0, 0, 0], 1.0, dev)
+    assert got[0].tolist() == [-1.0, -2.5, -2.0, -1.0]
+    rng = np.random.default_rng(1)
+    sizes = [1000, 10]
+    ups = random_updates(rng, sizes, 20, 0.5)
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    got, _, _ = run_gpu(ac, theta0, ups, [max(0, q - 1) for q in range(20)], 0.01, dev)
+    sgd = [t.copy() for t in theta0]
+    for o, i, v in ups:
+        for l in range(2):
+            sl = slice(int(o[l]), int(o[l + 1]))
+            sgd[l][i[sl]] = sgd[l][i[sl]] - np.float32(0.01) * v[sl]
+    assert all(np.array_equal(a, b) for a, b in zip(got, sgd))
+    dense = random_updates(rng, sizes, 12, 1.0)
+    dense = [(o, i, v + np.float32(3.0)) for o, i, v in dense]
+    stale = rng.integers(0, 6, 12).tolist()
+    pulls = [max(0, q - s) for q, s in enumerate(stale)]
+    got, _, _ = run_gpu(ac, theta0, dense, pulls, 0.05, dev)
+    ref = [t.copy() for t in theta0]
+    for q, (o, i, v) in enumerate(dense):
+        a = np.float32(0.05) / np.float32(max(1, q - pulls[q]))
+        for l in range(2):
+            ref[l] = (ref[l] - a * v[int(o[l]):int(o[l + 1])]).astype(np.float32)
+    assert all(np.array_equal(a, b) for a, b in zip(got, ref))
+
+
+def test_cnn_apply_config(ac, dev):
+    """Config 'PS apply for the small CNN': 200 queued 1% updates made by the oracle's own
+    selection from 200 seeded gradients, staleness uniform in [1, 200], lr 0.01."""
+    cfg, rate = "cnn_apply", 0.01
+    Q = workloads.CONFIGS[cfg]["Q"]
+    lr = workloads.CONFIGS[cfg]["lr"]
+    stale = workloads.staleness(cfg)
+    pulls = workloads.pull_timestamps(stale)
+    print("[apply] cnn: oracle selects 200 gradients", flush=True)
+    grads = [[x.numpy() for x in workloads.gradient(cfg, q)] for q in range(Q)]
+    ups = oracle_select_parallel(grads, rate, threads=12)
+    del grads
+    theta0 = [t.numpy() for t in workloads.theta0(cfg)]
+    print("[apply] cnn: gpu apply", flush=True)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, lr, dev)
+    assert st.t == Q
+    print("[apply] cnn: oracle apply", flush=True)
+    want = run_oracle(theta0, ups, pulls, lr, method=oracle.HISTORY_BITMAP)
+    assert compare(got, want, "cnn_apply vs fp32 oracle") == 0
+    want64 = run_oracle(theta0, ups, pulls, lr, method=oracle.HISTORY_BITMAP, f64=True)
+    for a, b in zip(got, want64):
+        assert np.all(np.abs(a - b) <= 3 * Q * 2.0 ** -24 * np.maximum(np.abs(b), 0.2))
+
+
+def test_mid_apply_config(ac, dev):
+    """Config 'mid-size CNN' at 1%: 64 queued updates, staleness uniform in [1, 64].  The six
+    tensors below 1M entries are checked in full against the oracle; the updates come from
+    the oracle's own selection."""
+    cfg, rate = "mid", 0.01
+    layers = [0, 1, 2, 3, 4, 7]
+    Q, lr = 64, workloads.CONFIGS[cfg]["lr"]
+    pulls = workloads.pull_timestamps(workloads.staleness(cfg))
+    grads = [[x.numpy() for x in workloads.gradient(cfg, q, layers=layers)] for q in range(Q)]
+    ups = oracle_select_parallel(grads, rate, threads=12)
+    theta0 = [t.numpy() for t in workloads.theta0(cfg, layers=layers)]
+    got, _, _ = run_gpu(ac, theta0, ups, pulls, lr, dev)
+    want = run_oracle(theta0, ups, pulls, lr)
+    assert compare(got, want, "mid apply") == 0
+
+
+def test_extreme_staleness_long_queue(ac, dev):
+    """Staleness 1 and 10^4 side by side: 10,050 queued updates of one entry per tensor (rate 1/N),
+    drawn from a handful of parameters per tensor so that sigma_k reaches the thousands."""
+    rng = np.random.default_rng(77)
+    sizes = workloads.sizes_of("adversarial")[:12]
+    Q = 10_050
+    ups = []
+    for q in range(Q):
+        idx = np.array([rng.integers(0, min(n, 3)) for n in sizes], dtype=np.uint32)
+        val = rng.standard_normal(len(sizes)).astype(np.float32)
+        ups.append((np.arange(len(sizes) + 1, dtype=np.uint64), idx, val))
+    stale = [1 if q % 2 else 10_000 for q in range(Q)]
+    pulls = workloads.pull_timestamps(stale)
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    print("[apply] long queue: gpu", flush=True)
+    got, cnt, st = run_gpu(ac, theta0, ups, pulls, 0.01, dev)
+    assert st.t == Q
+    print("[apply] long queue: oracle", flush=True)
+    want = run_oracle(theta0, ups, pulls, 0.01)
+    assert compare(got, want, "long queue") == 0
+    assert max(int(c.max()) for c in cnt) > 3000
+
+
+def test_flat_config_full_size_sampled(ac, dev):
+    """The roofline configuration as bench.py runs it: 100 tensors of 10M parameters, 16 queued
+    0.5% updates (selected on the GPU from 16 seeded 1B-element gradients), staleness uniform
+    in [1, 16].  The oracle replays three whole tensors (its own selection, its own apply); on
+    every tensor the touched-parameter counters must equal the number of updates holding them."""
+    cfg, rate = "flat", 0.005
+    sizes = workloads.sizes_of(cfg)
+    L, Q, lr = len(sizes), 16, workloads.CONFIGS[cfg]["lr"]
+    pulls = workloads.pull_timestamps(workloads.staleness(cfg))
+    sample = [0, 41, 99]
+    theta = workloads.theta0(cfg, device=dev)
+    theta0 = {l: theta[l].cpu().numpy().copy() for l in sample}
+    ups, host_g = [], {l: [] for l in sample}
+    ws = None
+    for q in range(Q):
+        print(f"[apply] flat: select update {q}", flush=True)
+        g = workloads.gradient(cfg, q, device=dev)
+        for l in sample:
+            host_g[l].append(g[l].cpu().numpy())
+        if ws is None:
+            ws = torch.empty(ac.adacomp_select_workspace(sizes, rate), dtype=torch.uint8, device=dev)
+        ups.append(gpu_select(ac, g, rate, pull_ts=pulls[q], ws=ws))
+        del g
+    st = ac.State(theta)
+    aws = torch.empty(ac.adacomp_apply_workspace(L, ups), dtype=torch.uint8, device=dev)
+    print("[apply] flat: gpu apply", flush=True)
+    ac.adacomp_apply(theta, st, ups, lr, aws)
+    torch.cuda.synchronize()
+    assert st.t == Q
+    k = ac.adacomp_count(sizes[0], rate)
+    for l in range(L):
+        ref = torch.zeros(sizes[l], dtype=torch.int32, device=dev)
+        for u in ups:
+            ref.index_add_(0, u.idx[l * k:(l + 1) * k].to(torch.int64),
+                           (u.val[l * k:(l + 1) * k] != 0).to(torch.int32))
+        assert torch.equal(ref, st.cnt[l]), f"tensor {l}: counters"
+    print("[apply] flat: oracle on sampled tensors", flush=True)
+    for l in sample:
+        o_ups = oracle_select_parallel([[x] for x in host_g[l]], rate, threads=8)
+        want = run_oracle([theta0[l]], o_ups, pulls, lr)
+        assert compare([theta[l].cpu().numpy()], want, f"flat tensor {l}") == 0

@@ -1,0 +1,191 @@
+"""GPU parity: adacomp_select (HIP, through the C ABI) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from helpers import assert_update_equal, gpu_select, oracle_select_parallel, update_to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ac():
+    import paper_1702_04683_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return torch.device("cuda:0")
+
+
+def host(tensors):
+    return [t.cpu().numpy() for t in tensors]
+
+
+def check(ac, tensors, rate, k_override=None, what=""):
+    print(f"[select] {what} rate={rate} k_override={'yes' if k_override else 'no'} "
+          f"sizes={[t.numel() for t in tensors][:8]}...", flush=True)
+    u = gpu_select(ac, tensors, rate, k_override)
+    want = oracle.select(host(tensors), rate, k_override)
+    assert_update_equal(update_to_host(u), want, what)
+    return u
+
+
+@pytest.mark.parametrize("rate", [0.01, 0.001, 0.1, 0.3, 1.0, 0.0])
+def test_cnn_config(ac, dev, rate):
+    """Config 'small CNN, one worker update': 8 tensors, heavy-tailed gradients."""
+    g = workloads.gradient("cnn_select", 0, device=dev)
+    check(ac, g, rate, what="cnn")
+
+
+def test_cnn_repeatable_and_workspace_reuse(ac, dev):
+    g = workloads.gradient("cnn_select", 1, device=dev)
+    ws = torch.empty(ac.adacomp_select_workspace([t.numel() for t in g], 0.01), dtype=torch.uint8, device=dev)
+    ws.fill_(0xAB)   # the workspace may hold anything on entry
+    runs = [update_to_host(gpu_select(ac, g, 0.01, ws=ws)) for _ in range(3)]
+    want = oracle.select(host(g), 0.01)
+    for r in runs:
+        assert_update_equal(r, want, "repeat")
+
+
+@pytest.mark.parametrize("rate", [0.001, 0.01, 0.1])
+def test_mid_config(ac, dev, rate):
+    """Config 'mid-size CNN': 57M Laplace gradients in 8 tensors."""
+    g = workloads.gradient("mid", 0, device=dev)
+    print(f"[select] mid rate={rate}", flush=True)
+    u = gpu_select(ac, g, rate)
+    want = oracle_select_parallel([[x] for x in host(g)], rate)
+    off, idx, val = update_to_host(u)
+    for l, (o, i, v) in enumerate(want):
+        a, b = int(off[l]), int(off[l + 1])
+        assert b - a == int(o[1])
+        assert np.array_equal(idx[a:b], i), f"tensor {l} indices"
+        assert np.array_equal(val[a:b].view(np.uint32), v.view(np.uint32)), f"tensor {l} values"
+
+
+def test_adversarial_config_k1_rate1_rate0(ac, dev):
+    """Config 'adversarial': 40 ragged tensors (two of one element), zeros, ties, +-duplicates,
+    denormals; rates 0, 1/N (as k_override = 1 and as rate = 1/N on single tensors) and 100%."""
+    g = workloads.gradient("adversarial", 0, device=dev)
+    sizes = [t.numel() for t in g]
+    assert sizes.count(1) >= 2 and all(n % 64 for n in sizes)
+    L = len(g)
+    # rate 0: nothing selected
+    u = gpu_select(ac, g, 0.0)
+    assert u.total == 0 and u.offsets == [0] * (L + 1)
+    # k = 1 per tensor through k_override
+    print("[select] adversarial k_override=1", flush=True)
+    u = gpu_select(ac, g, 0.5, k_override=[1] * L)
+    hg = host(g)
+    want = oracle_select_parallel([[x] for x in hg], 0.5, k_override=[1])
+    off, idx, val = update_to_host(u)
+    for l, (o, i, v) in enumerate(want):
+        assert idx[l] == i[0] and val[l:l + 1].view(np.uint32)[0] == v.view(np.uint32)[0], f"tensor {l}"
+    # rate = 1/N on single tensors
+    for l in (0, 3, 7, L - 2):
+        check(ac, [g[l]], 1.0 / sizes[l], what=f"adversarial 1/N tensor {l}")
+    # rate 1: identity; the oracle is consulted on the tensors below 1M entries, the definition on all
+    print("[select] adversarial rate=1", flush=True)
+    u = gpu_select(ac, g, 1.0)
+    off, idx, val = update_to_host(u)
+    assert off.tolist() == np.cumsum([0] + sizes).tolist()
+    for l in range(L):
+        a, b = int(off[l]), int(off[l + 1])
+        assert np.array_equal(idx[a:b], np.arange(sizes[l], dtype=np.uint32))
+        assert np.array_equal(val[a:b].view(np.uint32), hg[l].view(np.uint32))
+        if sizes[l] < 1_000_000:
+            i, v = oracle.select_layer(hg[l], sizes[l])
+            assert np.array_equal(idx[a:b], i)
+
+
+@pytest.mark.parametrize("rate", [0.01, 0.3, 0.0007, 0.6])
+def test_adversarial_ties_at_threshold(ac, dev, rate):
+    """Runs of identical magnitudes planted at the 1% and 30% quantiles: the threshold falls
+    inside a run and the lower indices must win."""
+    sizes = workloads.sizes_of("adversarial")
+    pick = [l for l, n in enumerate(sizes) if n < 2_000_000][:10]
+    g = [workloads.gradient_layer("adversarial", 0, l, sizes[l], dev) for l in pick]
+    check(ac, g, rate, what="adversarial ties")
+
+
+def test_degenerate_tensors(ac, dev):
+    n = 300_007
+    ones = torch.ones(n, device=dev)
+    ones[::3] = -1.0
+    zeros = torch.zeros(n, device=dev)
+    zeros[1::2] = -0.0
+    ramp = torch.arange(n, device=dev, dtype=torch.float32)
+    two_level = torch.where(torch.arange(n, device=dev) % 7 == 0, 2.0, 1.0)
+    one = torch.tensor([-3.5], device=dev)
+    empty = torch.empty(0, device=dev)
+    tiny = torch.tensor([1e-45, -1e-45, 0.0, 3e-39, -3e-39], device=dev)
+    special = torch.tensor([1.0, float("-inf"), 3e38, float("nan"), 0.0, float("inf"), 1e-45], device=dev)
+    tensors = [ones, zeros, ramp, two_level, one, empty, tiny, special, ramp.flip(0).contiguous()]
+    for rate in (0.01, 0.2, 0.5, 0.9):
+        check(ac, tensors, rate, what="degenerate")
+    check(ac, tensors, 0.5, k_override=[1, 2, 3, n - 1, 1, 0, 4, 3, n // 2], what="degenerate k_override")
+
+
+def test_clustered_large_values_fall_back_to_the_dense_source(ac, dev):
+    """All large entries sit in one contiguous stretch, so wave segments there overflow their
+    candidate regions while a strided sample misjudges the threshold: the result must stay exact."""
+    n = 2_000_003
+    gen = torch.Generator(device=dev).manual_seed(11)
+    g = torch.randn(n, generator=gen, device=dev) * 1e-3
+    g[700_001:700_001 + 30_000] = torch.randn(30_000, generator=gen, device=dev)
+    h = torch.randn(n, generator=gen, device=dev) * 1e-3
+    h[::8192] *= 1000.0      # large entries only where a strided sample rarely looks
+    for rate in (0.01, 0.002):
+        check(ac, [g, h], rate, what="clustered")
+
+
+def test_unaligned_tensor_views(ac, dev):
+    """Tensors that start 4, 8 or 12 bytes past a 16-byte boundary take the scalar load path."""
+    base = workloads.gradient_layer("cnn_select", 2, 4, 3211264, dev)
+    views = [base[1:1_000_000], base[2:777_779], base[3:50_001], base[5:6]]
+    assert all(v.data_ptr() % 16 != 0 for v in views)
+    check(ac, [v for v in views], 0.01, what="unaligned")
+    check(ac, [v for v in views], 0.4, what="unaligned dense")
+
+
+def test_negation_and_scaling_invariance_on_gpu(ac, dev):
+    g = workloads.gradient("cnn_select", 2, device=dev)
+    a = update_to_host(gpu_select(ac, g, 0.01))
+    b = update_to_host(gpu_select(ac, [-x for x in g], 0.01))
+    c = update_to_host(gpu_select(ac, [x * 4.0 for x in g], 0.01))
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], -b[2])
+    assert np.array_equal(a[1], c[1]) and np.array_equal(a[2] * np.float32(4.0), c[2])
+
+
+def test_flat_config_full_size(ac, dev):
+    """The roofline configuration in the launch shape bench.py times: 100 tensors of 10M entries,
+    rate 0.5%, one call.  The oracle checks sampled tensors entry by entry; on all 100 the
+    properties that define a correct selection are evaluated with torch on the device."""
+    cfg, rate = "flat", 0.005
+    sizes = workloads.sizes_of(cfg)
+    g = workloads.gradient(cfg, 0, device=dev)
+    print("[select] flat full size, 1e9 elements", flush=True)
+    u = gpu_select(ac, g, rate)
+    k = ac.adacomp_count(sizes[0], rate)
+    assert u.offsets == [k * l for l in range(len(sizes) + 1)] and k == 50_000
+    for l in (0, 37, 99):
+        i, v = oracle.select_layer(g[l].cpu().numpy(), k)
+        assert np.array_equal(u.idx[l * k:(l + 1) * k].cpu().numpy().view(np.uint32), i), f"tensor {l}"
+        assert np.array_equal(u.val[l * k:(l + 1) * k].cpu().numpy().view(np.uint32), v.view(np.uint32))
+    for l in range(len(sizes)):
+        idx = u.idx[l * k:(l + 1) * k].to(torch.int64)
+        val = u.val[l * k:(l + 1) * k]
+        assert bool((idx[1:] > idx[:-1]).all()) and int(idx[-1]) < sizes[l] and int(idx[0]) >= 0
+        assert torch.equal(g[l][idx].view(torch.int32), val.view(torch.int32))
+        key = g[l].view(torch.int32) & 0x7FFFFFFF
+        T = int((val.view(torch.int32) & 0x7FFFFFFF).min())
+        n_gt, n_ge = int((key > T).sum()), int((key >= T).sum())
+        assert n_gt < k <= n_ge, f"tensor {l}: threshold is not the k-th largest magnitude"
+        sel_key = key[idx]
+        assert int((sel_key > T).sum()) == n_gt, f"tensor {l}: an entry above the threshold is missing"
+        eq_all = torch.nonzero(key == T).flatten()[:k - n_gt]
+        assert torch.equal(idx[sel_key == T], eq_all), f"tensor {l}: tie rule"
