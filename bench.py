@@ -1,0 +1,173 @@
+"""Throughput of AdaComp's data-parallel hot path on one MI355X.
+
+Workload ("flat", the roofline configuration): a stream of 1B-element fp32 gradients in
+100 tensors of 10M, mixture 95% N(0,1e-5) + 5% N(0,1e-2), rate 0.5% per tensor, 16
+queued worker updates with staleness uniform in [1,16].  One step = one pass of the
+whole path over one batch of 16 worker gradients, all resident in HBM: 16 x
+adacomp_select (one per gradient), then one adacomp_apply of the 16-update queue.
+value = gradient elements compressed and applied per second = 16e9 / step time.
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel (select's streaming filter
+pass), timed live with HIP events on the launch stream inside the timed steps;
+`cpu_baseline` is the CPU oracle as it stands, single thread, on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(cfg, rate, lr, pulls, n_updates=4, layer=0):
+    """Oracle select + apply of `n_updates` worker updates on one 10M-entry tensor."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    grads = [workloads.gradient_layer(cfg, q, layer).numpy() for q in range(n_updates)]
+    theta = [workloads.theta0(cfg, layers=[layer])[0].numpy().copy()]
+    ps = oracle.ParameterServer(theta)
+    t0 = time.perf_counter()
+    for q in range(n_updates):
+        off, idx, val = oracle.select([grads[q]], rate)
+        ps.apply(off, idx, val, min(pulls[q], q), lr)
+    dt = time.perf_counter() - t0
+    elems = n_updates * grads[0].size
+    return {"value": elems / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"{n_updates} worker updates of one 10M-entry tensor of the flat workload "
+                      f"(select at {rate}, then PS apply), {dt:.1f} s of single-thread C"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also time every kernel in one extra untimed step")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 4 GB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+
+    import paper_1702_04683_amd as ac
+    import workloads
+
+    ac.load_library()   # raises if libadacomp.so is not built: there is no fallback path
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    cfg = "flat"
+    c = workloads.CONFIGS[cfg]
+    rate, lr, Q = c["rates"][0], c["lr"], c["Q"]
+    sizes = workloads.sizes_of(cfg)
+    L, N = len(sizes), sum(sizes)
+    pulls = workloads.pull_timestamps(workloads.staleness(cfg))
+
+    grads = [workloads.gradient(cfg, q, device=dev) for q in range(Q)]      # 16 x 4 GB resident
+    theta = workloads.theta0(cfg, device=dev)
+    state = ac.State(theta)
+    cap = sum(ac.adacomp_count(n, rate) for n in sizes)
+    updates = [ac.Update(L, cap, dev) for _ in range(Q)]
+    sel_ws = torch.empty(ac.adacomp_select_workspace(sizes, rate), dtype=torch.uint8, device=dev)
+    for q in range(Q):      # fills layer_off so that the apply workspace can be sized
+        ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
+    app_ws = torch.empty(ac.adacomp_apply_workspace(L, updates), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def step():
+        t0 = state.t
+        for q in range(Q):
+            updates[q].pull_ts = t0 + pulls[q]
+            ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
+        ac.adacomp_apply(theta, state, updates, lr, app_ws)
+
+    if args.copy_calibration:     # reads 4e9 bytes, writes 4e9 bytes
+        src = torch.cat([g.view(-1) for g in grads[0]])
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ac.adacomp_profile_start({"filter"})
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    prof = ac.adacomp_profile_stop()
+
+    sec = t_end - t_begin
+    ms_per_step = 1e3 * sec / args.steps
+    value = Q * N * args.steps / sec
+
+    f_ms, f_n = prof["filter"]
+    f_avg_s = 1e-3 * f_ms / f_n
+    alg_bytes = 4.0 * N + 8.0 * cap           # per launch: every element read once, every selected pair written
+    achieved = alg_bytes / f_avg_s / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "filter_flat_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    out = {
+        "metric": "gradient elements/sec compressed+applied",
+        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "flat: 100 tensors x 10M fp32 = 1e9 elements per worker gradient, "
+                               "95% N(0,1e-5) + 5% N(0,1e-2), rate 0.5% per tensor, 16 queued updates, "
+                               "staleness U[1,16]; step = 16 selects + 1 apply of the queue",
+                   "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q},
+        "roofline": {"bound": "hbm", "kernel": "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": 1e3 * f_avg_s,
+                     "launches": f_n},
+    }
+
+    # split of the step between the two halves (untimed extra steps, whole-call events)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    kernels = None
+    if args.breakdown:
+        ac.adacomp_profile_start(None)
+    ev[0].record()
+    t0 = state.t
+    for q in range(Q):
+        updates[q].pull_ts = t0 + pulls[q]
+        ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
+    ev[1].record()
+    ac.adacomp_apply(theta, state, updates, lr, app_ws)
+    ev[2].record()
+    torch.cuda.synchronize()
+    if args.breakdown:
+        kernels = {k: {"ms_total": round(v[0], 4), "launches": v[1]} for k, v in ac.adacomp_profile_stop().items()}
+    sel_ms, app_ms = ev[0].elapsed_time(ev[1]) / Q, ev[1].elapsed_time(ev[2])
+    out["select_ms_per_update"] = sel_ms
+    out["apply_ms_per_queue"] = app_ms
+    out["select_algorithmic_frac_of_peak"] = (4.0 * N + 8.0 * cap) / (sel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    out["apply_entries_per_s"] = Q * cap / (app_ms * 1e-3)
+    if kernels:
+        out["kernels"] = kernels
+
+    if not args.no_cpu_baseline:
+        del grads
+        out["cpu_baseline"] = cpu_baseline(cfg, rate, lr, pulls)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -14,10 +14,11 @@
  * Conventions common to all calls
  *   - "DEVICE" pointers are HIP device memory of the current device, "HOST" pointers
  *     ordinary host memory.  Every buffer is allocated and owned by the caller; the
- *     library allocates no device memory, keeps no global state and never
- *     synchronises the device.  All device work is enqueued on `hip_stream`
- *     (a hipStream_t passed as void*, NULL = the default stream) and is complete
- *     when that stream has drained.  Host arrays are read before the call returns.
+ *     library allocates no device memory, keeps no global state (the optional event
+ *     timing at the end of this header aside) and never synchronises the device.
+ *     All device work is enqueued on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and is complete when that stream has drained.
+ *     Host arrays are read before the call returns.
  *   - Return value 0 on success, a negative ADACOMP_ERR_* otherwise.  Arguments are
  *     checked before anything is enqueued: a failing call has no side effect.
  *   - Sizes are in elements unless a name says bytes.  A tensor has at most
@@ -160,6 +161,40 @@ int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, adacomp_state
 
 /* Static, human-readable text for a return code. */
 const char *adacomp_strerror(int code);
+
+/* ---- measurement aid (not an operation of the paper) -------------------------------
+ * Kernels of the library, for the optional event timing below. */
+enum {
+    ADACOMP_KERNEL_PUT = 0,        /* small host->device table upload through kernel arguments */
+    ADACOMP_KERNEL_FILL,           /* clear histograms                                          */
+    ADACOMP_KERNEL_SAMPLE_HIST,    /* select: histogram of a strided sample                     */
+    ADACOMP_KERNEL_PICK,           /* select: choose the filter threshold                       */
+    ADACOMP_KERNEL_FILTER,         /* select: streaming read + ordered candidate compaction     */
+    ADACOMP_KERNEL_CHECK,          /* select: candidates sufficient?                            */
+    ADACOMP_KERNEL_HIST,           /* select: radix-descent histogram (3 levels)                */
+    ADACOMP_KERNEL_RESOLVE,        /* select: radix-descent bin choice (3 levels)               */
+    ADACOMP_KERNEL_COUNT_SEG,      /* select: per-segment counts above / at the threshold       */
+    ADACOMP_KERNEL_SCAN,           /* select: exclusive scan of the segment counts              */
+    ADACOMP_KERNEL_EMIT,           /* select: ordered write of the (index, value) pairs         */
+    ADACOMP_KERNEL_IDENTITY,       /* select: k == n copy                                       */
+    ADACOMP_KERNEL_SNAPSHOT,       /* apply: counter reading at pull time                       */
+    ADACOMP_KERNEL_SCATTER_APPLY,  /* apply: eqs. 3-5 scatter                                   */
+    ADACOMP_KERNEL_COUNT
+};
+
+/* Start timing every launch of the kernels whose bit (1 << ADACOMP_KERNEL_*) is set in
+ * kernel_mask: a HIP event is recorded before and after each such launch on the stream
+ * the kernel is enqueued on.  The only process-global state of the library; not
+ * thread-safe.  Events are host objects; no device memory is allocated. */
+int adacomp_profile_start(uint64_t kernel_mask);
+
+/* Stop timing, wait for the recorded events and report, per kernel id, the summed
+ * duration in milliseconds and the number of launches.  total_ms, launches: HOST arrays
+ * of ADACOMP_KERNEL_COUNT elements (either may be NULL). */
+int adacomp_profile_stop(double *total_ms, uint64_t *launches);
+
+/* Short static name of a kernel id. */
+const char *adacomp_kernel_name(int id);
 
 #ifdef __cplusplus
 }

@@ -14,6 +14,9 @@ from .binding import (  # noqa: F401
     adacomp_apply_workspace,
     adacomp_apply,
     adacomp_strerror,
+    adacomp_kernel_name,
+    adacomp_profile_start,
+    adacomp_profile_stop,
     library_path,
     load_library,
 )

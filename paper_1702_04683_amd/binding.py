@@ -67,6 +67,12 @@ def load_library():
                                   C.c_float, vp, sz, vp]
     lib.adacomp_strerror.restype = C.c_char_p
     lib.adacomp_strerror.argtypes = [C.c_int]
+    lib.adacomp_profile_start.restype = C.c_int
+    lib.adacomp_profile_start.argtypes = [u64]
+    lib.adacomp_profile_stop.restype = C.c_int
+    lib.adacomp_profile_stop.argtypes = [C.POINTER(C.c_double), C.POINTER(u64)]
+    lib.adacomp_kernel_name.restype = C.c_char_p
+    lib.adacomp_kernel_name.argtypes = [C.c_int]
     _lib = lib
     return lib
 
@@ -197,3 +203,32 @@ def adacomp_apply(params, state, updates, lr, workspace, stream=None):
     if rc:
         raise AdaCompError(rc, "adacomp_apply")
     return state
+
+
+KERNEL_COUNT = 14
+
+
+def adacomp_kernel_name(kernel_id):
+    return load_library().adacomp_kernel_name(int(kernel_id)).decode()
+
+
+def adacomp_profile_start(kernels=None):
+    """Time the launches of the named kernels (all if None) with HIP events."""
+    names = [adacomp_kernel_name(i) for i in range(KERNEL_COUNT)]
+    mask = 0
+    for i, nm in enumerate(names):
+        if kernels is None or nm in kernels:
+            mask |= 1 << i
+    rc = load_library().adacomp_profile_start(mask)
+    if rc:
+        raise AdaCompError(rc, "adacomp_profile_start")
+
+
+def adacomp_profile_stop():
+    """-> {kernel name: (total milliseconds, launches)} for the kernels that ran."""
+    ms = (C.c_double * KERNEL_COUNT)()
+    cnt = (C.c_uint64 * KERNEL_COUNT)()
+    rc = load_library().adacomp_profile_stop(ms, cnt)
+    if rc:
+        raise AdaCompError(rc, "adacomp_profile_stop")
+    return {adacomp_kernel_name(i): (float(ms[i]), int(cnt[i])) for i in range(KERNEL_COUNT) if cnt[i]}

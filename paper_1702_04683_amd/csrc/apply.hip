@@ -182,8 +182,8 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
             const adacomp_update_t &u = updates[w];
             const uint64_t total = u.layer_off[L];
             const unsigned grid = (unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS));
-            hipLaunchKernelGGL(k_snapshot, dim3(grid), dim3(BLOCK), 0, s, P, L, u.layer_off_dev, u.idx,
-                               reinterpret_cast<uint32_t *>(wsb + lay.snap[w]), total);
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_SNAPSHOT, k_snapshot, dim3(grid), dim3(BLOCK), s, P, L,
+                           u.layer_off_dev, u.idx, reinterpret_cast<uint32_t *>(wsb + lay.snap[w]), total);
             if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
         }
         const adacomp_update_t &u = updates[q];
@@ -192,11 +192,11 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         const unsigned grid = (unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS));
         const uint32_t *snap = reinterpret_cast<const uint32_t *>(wsb + lay.snap[q]);
         if (stale[q])
-            hipLaunchKernelGGL(k_scatter_apply<true>, dim3(grid), dim3(BLOCK), 0, s, P, L, u.layer_off_dev,
-                               u.idx, u.val, snap, total, lr);
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, k_scatter_apply<true>, dim3(grid), dim3(BLOCK), s, P, L,
+                           u.layer_off_dev, u.idx, u.val, snap, total, lr);
         else
-            hipLaunchKernelGGL(k_scatter_apply<false>, dim3(grid), dim3(BLOCK), 0, s, P, L, u.layer_off_dev,
-                               u.idx, u.val, snap, total, lr);
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, k_scatter_apply<false>, dim3(grid), dim3(BLOCK), s, P, L,
+                           u.layer_off_dev, u.idx, u.val, snap, total, lr);
         if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
     }
     st->t = t0 + Q;

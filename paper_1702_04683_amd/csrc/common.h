@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "adacomp.h"
@@ -37,5 +38,28 @@ hipError_t put_async(void *dst_dev, const void *src_host, size_t bytes, hipStrea
 
 // dst[i] = value for i < n (32-bit words)
 hipError_t fill_u32_async(uint32_t *dst_dev, uint32_t value, size_t n, hipStream_t s);
+
+// Start/stop events for one kernel dispatch when timing of kernel `id` is switched on.
+class ProfScope {
+public:
+    explicit ProfScope(int id);
+    bool active() const { return beg_ != nullptr; }
+    hipEvent_t beg() const { return beg_; }
+    hipEvent_t end() const { return end_; }
+
+private:
+    hipEvent_t beg_, end_;
+};
+
+// Launch `kernel` on stream `s`; with timing on, the dispatch carries its own events.
+#define ADACOMP_LAUNCH(id, kernel, grid, block, s, ...)                                       \
+    do {                                                                                      \
+        ::adacomp::ProfScope prof_scope_(id);                                                 \
+        if (prof_scope_.active())                                                             \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, s, prof_scope_.beg(), prof_scope_.end(), 0, \
+                                  __VA_ARGS__);                                               \
+        else                                                                                  \
+            hipLaunchKernelGGL(kernel, grid, block, 0, s, __VA_ARGS__);                       \
+    } while (0)
 
 }  // namespace adacomp

@@ -704,8 +704,8 @@ hipError_t put_async(void *dst_dev, const void *src_host, size_t bytes, hipStrea
         const size_t nb = std::min<size_t>(nw * 8, bytes - w0 * 8);
         a.w[nw - 1] = 0;
         std::memcpy(a.w, src + w0 * 8, nb);
-        hipLaunchKernelGGL(k_put, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s,
-                           static_cast<uint64_t *>(dst_dev) + w0, a, (uint32_t)nw);
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_PUT, k_put, dim3((unsigned)((nw + 255) / 256)), dim3(256), s,
+                       static_cast<uint64_t *>(dst_dev) + w0, a, (uint32_t)nw);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -715,7 +715,7 @@ hipError_t put_async(void *dst_dev, const void *src_host, size_t bytes, hipStrea
 hipError_t fill_u32_async(uint32_t *dst_dev, uint32_t value, size_t n, hipStream_t s) {
     if (n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)std::min<size_t>((n + 1023) / 1024, 4096);
-    hipLaunchKernelGGL(k_fill, dim3(blocks), dim3(256), 0, s, dst_dev, value, n);
+    ADACOMP_LAUNCH(ADACOMP_KERNEL_FILL, k_fill, dim3(blocks), dim3(256), s, dst_dev, value, n);
     return hipGetLastError();
 }
 
@@ -746,10 +746,10 @@ extern "C" int adacomp_select_workspace(const uint64_t *n, uint32_t L, double ra
     return ADACOMP_OK;
 }
 
-#define LAUNCH(kernel, grid, ...)                                                   \
+#define LAUNCH(id, kernel, grid, ...)                                               \
     do {                                                                            \
         if ((grid) > 0) {                                                           \
-            hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(BLOCK), 0, s, __VA_ARGS__); \
+            ADACOMP_LAUNCH(id, kernel, dim3((unsigned)(grid)), dim3(BLOCK), s, __VA_ARGS__); \
             if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;            \
         }                                                                           \
     } while (0)
@@ -792,24 +792,24 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
     const LayerDesc &tot = plan.desc[L];
     uint32_t *out_idx = out->idx;
     uint32_t *out_val = reinterpret_cast<uint32_t *>(out->val);
-    LAUNCH(k_sample_hist, tot.sblk_base, ws, L);
-    LAUNCH(k_pick, L, ws);
+    LAUNCH(ADACOMP_KERNEL_SAMPLE_HIST, k_sample_hist, tot.sblk_base, ws, L);
+    LAUNCH(ADACOMP_KERNEL_PICK, k_pick, L, ws);
     if (tot.sblk_base) {  // at least one tensor goes through the filter
-        LAUNCH(k_filter, tot.wblk_base, ws, L);
-        LAUNCH(k_check, L, ws);
+        LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, tot.wblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_CHECK, k_check, L, ws);
     }
     if (tot.seg_base) {
-        LAUNCH(k_hist<0>, tot.hblk_base, ws, L);
-        LAUNCH(k_resolve<0>, L, ws);
-        LAUNCH(k_hist<1>, tot.hblk_base, ws, L);
-        LAUNCH(k_resolve<1>, L, ws);
-        LAUNCH(k_hist<2>, tot.hblk_base, ws, L);
-        LAUNCH(k_resolve<2>, L, ws);
-        LAUNCH(k_count, tot.wblk_base, ws, L);
-        LAUNCH(k_scan, L, ws);
-        LAUNCH(k_emit, tot.wblk_base, ws, L, out_idx, out_val);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<0>, tot.hblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<0>, L, ws);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<1>, tot.hblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<1>, L, ws);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<2>, tot.hblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<2>, L, ws);
+        LAUNCH(ADACOMP_KERNEL_COUNT_SEG, k_count, tot.wblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_SCAN, k_scan, L, ws);
+        LAUNCH(ADACOMP_KERNEL_EMIT, k_emit, tot.wblk_base, ws, L, out_idx, out_val);
     }
-    LAUNCH(k_identity, tot.iblk_base, ws, L, out_idx, out_val);
+    LAUNCH(ADACOMP_KERNEL_IDENTITY, k_identity, tot.iblk_base, ws, L, out_idx, out_val);
     return ADACOMP_OK;
 }
 
