@@ -82,7 +82,7 @@ def main():
     sel_ws = torch.empty(ac.adacomp_select_workspace(sizes, rate), dtype=torch.uint8, device=dev)
     for q in range(Q):      # fills layer_off so that the apply workspace can be sized
         ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
-    app_ws = torch.empty(ac.adacomp_apply_workspace(L, updates), dtype=torch.uint8, device=dev)
+    app_ws = torch.empty(ac.adacomp_apply_workspace(sizes, updates), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     def step():

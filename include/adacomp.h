@@ -134,9 +134,10 @@ int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double rate,
                    void *workspace, size_t ws_bytes, void *hip_stream);
 
 /* Bytes of DEVICE workspace adacomp_apply needs for a queue of Q updates (HOST
- * array; only num_layers and layer_off are read) on L parameter tensors. */
-int adacomp_apply_workspace(uint32_t L, const adacomp_update_t *updates, uint32_t Q,
-                            size_t *bytes);
+ * array; only num_layers and layer_off are read) on L parameter tensors of sizes
+ * n[0..L) (HOST).  Depends on these sizes only. */
+int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
+                            uint32_t Q, size_t *bytes);
 
 /* Parameter-server iterations (Alg. 2, loop body) for a queue: updates[0..Q) are
  * applied in array order as iterations i = st->t, st->t + 1, ...; for each entry
@@ -154,7 +155,11 @@ int adacomp_apply_workspace(uint32_t L, const adacomp_update_t *updates, uint32_
  *            st->t <= pull_ts <= apply time of that update, else
  *            ADACOMP_ERR_HISTORY / ADACOMP_ERR_FUTURE_PULL
  *   lr       alpha, finite
- *   workspace DEVICE, 256-byte aligned, >= adacomp_apply_workspace() bytes */
+ *   workspace DEVICE, 256-byte aligned, >= adacomp_apply_workspace() bytes
+ * The queue is executed either update by update (scatter) or in one sweep over
+ * coordinate tiles; the choice is made from the sizes and does not change the result.
+ * The environment variable ADACOMP_APPLY_PLAN=scatter|sweep, read by this call and by
+ * adacomp_apply_workspace, overrides it. */
 int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, adacomp_state_t *st,
                   const adacomp_update_t *updates, uint32_t Q, float lr,
                   void *workspace, size_t ws_bytes, void *hip_stream);
@@ -178,7 +183,10 @@ enum {
     ADACOMP_KERNEL_EMIT,           /* select: ordered write of the (index, value) pairs         */
     ADACOMP_KERNEL_IDENTITY,       /* select: k == n copy                                       */
     ADACOMP_KERNEL_SNAPSHOT,       /* apply: counter reading at pull time                       */
-    ADACOMP_KERNEL_SCATTER_APPLY,  /* apply: eqs. 3-5 scatter                                   */
+    ADACOMP_KERNEL_SCATTER_APPLY,  /* apply: eqs. 3-5 scatter, one update                       */
+    ADACOMP_KERNEL_BOUNDS,         /* apply: slice of every update per coordinate tile          */
+    ADACOMP_KERNEL_SWEEP,          /* apply: eqs. 3-5 for the whole queue, tile by tile         */
+    ADACOMP_KERNEL_SWEEP_SLOW,     /* apply: tiles whose touch lists exceed LDS                 */
     ADACOMP_KERNEL_COUNT
 };
 

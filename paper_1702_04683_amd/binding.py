@@ -61,7 +61,7 @@ def load_library():
     lib.adacomp_select.argtypes = [C.POINTER(_Layer), u32, C.c_double, C.POINTER(u64), C.POINTER(_Update),
                                    vp, sz, vp]
     lib.adacomp_apply_workspace.restype = C.c_int
-    lib.adacomp_apply_workspace.argtypes = [u32, C.POINTER(_Update), u32, C.POINTER(sz)]
+    lib.adacomp_apply_workspace.argtypes = [C.POINTER(u64), u32, C.POINTER(_Update), u32, C.POINTER(sz)]
     lib.adacomp_apply.restype = C.c_int
     lib.adacomp_apply.argtypes = [C.POINTER(_Layer), u32, C.POINTER(_State), C.POINTER(_Update), u32,
                                   C.c_float, vp, sz, vp]
@@ -184,10 +184,11 @@ def adacomp_select(layers, rate, out, workspace, k_override=None, stream=None):
     return out
 
 
-def adacomp_apply_workspace(num_layers, updates):
+def adacomp_apply_workspace(sizes, updates):
+    """Workspace bytes for applying `updates` to parameter tensors of the given sizes."""
     out = C.c_size_t(0)
     arr = (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
-    rc = load_library().adacomp_apply_workspace(int(num_layers), arr, len(updates), C.byref(out))
+    rc = load_library().adacomp_apply_workspace(_u64_array(sizes), len(sizes), arr, len(updates), C.byref(out))
     if rc:
         raise AdaCompError(rc, "adacomp_apply_workspace")
     return int(out.value)
@@ -205,7 +206,7 @@ def adacomp_apply(params, state, updates, lr, workspace, stream=None):
     return state
 
 
-KERNEL_COUNT = 14
+KERNEL_COUNT = 17
 
 
 def adacomp_kernel_name(kernel_id):

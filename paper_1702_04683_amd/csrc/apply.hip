@@ -2,12 +2,32 @@
 //
 // Per-parameter staleness without searching a history: cnt[k] counts the applied
 // updates whose entry for parameter k was non-zero, so the sum of indicators of eq. 3
-// over u = j .. i-1 is cnt_k(at time i) - cnt_k(at time j).  The index set of every
-// queued update is known when the call starts, so the second reading is taken by a
-// gather ("snapshot") of cnt at the update's own indices, enqueued at the point of the
-// queue where PS time equals the update's pull timestamp j.  Indices inside one update
-// are unique, so the scatter needs no atomics; updates are serialised by stream order.
+// over u = j .. i-1 is cnt_k(at time i) - cnt_k(at time j).
+//
+// Two execution plans, chosen on the host from sizes alone:
+//
+//   scatter  one launch per update, in queue order.  The reading cnt_k(j) is taken by a
+//            gather ("snapshot") of cnt at the update's own indices, enqueued where PS
+//            time equals the update's pull timestamp.  Indices inside one update are
+//            unique, so the scatter needs no atomics.  Each random 4-byte access moves a
+//            whole cache line: right for short or very sparse queues.
+//
+//   sweep    one launch for the whole queue.  Parameters are independent of each other
+//            (the result for k depends only on the touches of k, in time order), so a
+//            workgroup owns a tile of consecutive coordinates, collects the slices of
+//            all Q sorted index lists that fall into its tile (slice bounds come from a
+//            bisection kernel), groups them by coordinate with a counting sort in LDS,
+//            and replays every coordinate's touches in time order in registers.  For a
+//            touch by update q pulled at j, sigma_k is the number of earlier non-zero
+//            touches of k by updates u with j <= u < q: eq. 3 evaluated on the tile's own
+//            lists.  Theta and cnt are read and written once per touched line instead of
+//            once per touch.  A tile whose lists do not fit LDS is replayed update by
+//            update from global memory by a second kernel (snapshot scheme, one
+//            workgroup per such tile).
+#include <algorithm>
 #include <cmath>
+#include <cstdlib>
+#include <cstring>
 #include <vector>
 
 #include "common.h"
@@ -16,14 +36,43 @@ namespace adacomp {
 namespace {
 
 constexpr uint32_t BLOCK = 256;
-constexpr uint32_t ITEMS = 4;  // entries per thread
+constexpr uint32_t WAVES = BLOCK / WAVE;
+constexpr uint32_t ITEMS = 4;          // scatter plan: entries per thread
+constexpr uint32_t TILE_MAX = 4096;    // sweep plan: coordinates per tile (power of two, >= BLOCK)
+constexpr uint32_t STAGE_CAP = 2048;   // sweep plan: entries of the whole queue a tile can hold in LDS
+constexpr uint32_t LIST_MAX = 128;     // sweep plan: touches of one coordinate the fast kernel replays
+constexpr uint32_t SLOW_GRID = 1024;
 
 struct ParamDesc {
     float *theta;
     uint32_t *cnt;
     uint64_t n;
+    uint64_t tile_base;  // sweep plan: first tile of this tensor (entry L: number of tiles)
 };
 static_assert(sizeof(ParamDesc) % 8 == 0, "table is uploaded as 64-bit words");
+
+struct UpdDesc {
+    const uint32_t *idx;
+    const float *val;
+    const uint64_t *off;  // layer_off_dev
+    uint32_t *snap;       // scratch: counter readings at pull time, one per entry
+    uint32_t pull;        // pull timestamp relative to the first update of the call
+    uint32_t pad;
+};
+static_assert(sizeof(UpdDesc) % 8 == 0, "table is uploaded as 64-bit words");
+
+// eqs. 5 and 4 for one entry: one divide, one multiply, one subtract, each rounded once.
+__device__ __forceinline__ float step(float theta, float lr, uint32_t sigma, float v) {
+    float alpha = lr;
+    if (sigma != 0) alpha = __fdiv_rn(lr, (float)sigma);
+    return __fsub_rn(theta, __fmul_rn(alpha, v));
+}
+
+__device__ __forceinline__ bool is_nonzero(float v) {  // indicator of eq. 3
+    return (__float_as_uint(v) & KEY_MASK) != 0;
+}
+
+// ------------------------------------------------------------------ scatter plan
 
 // Tensor that holds entry e: the last l with off[l] <= e.
 __device__ __forceinline__ uint32_t layer_of(const uint64_t *off, uint32_t L, uint64_t e) {
@@ -64,23 +113,275 @@ __global__ __launch_bounds__(BLOCK) void k_scatter_apply(const ParamDesc *P, uin
         while (e >= off[l + 1]) ++l;
         const uint32_t k = idx[e];
         const float v = val[e];
-        const bool nonzero = (__float_as_uint(v) & KEY_MASK) != 0;  // indicator of eq. 3
+        const bool nonzero = is_nonzero(v);
         float *theta = P[l].theta + k;
         uint32_t *cnt = P[l].cnt + k;
-        float alpha = lr;
-        uint32_t c = 0;
+        uint32_t c = 0, sigma = 0;
         if (STALE || nonzero) c = *cnt;
-        if (STALE) {
-            const uint32_t sigma = c - snap[e];                      // eq. 3
-            if (sigma != 0) alpha = __fdiv_rn(lr, (float)sigma);     // eq. 5
-        }
-        *theta = __fsub_rn(*theta, __fmul_rn(alpha, v));             // eq. 4
+        if (STALE) sigma = c - snap[e];  // eq. 3
+        *theta = step(*theta, lr, sigma, v);
         if (nonzero) *cnt = c + 1;
     }
 }
 
+// ------------------------------------------------------------------ sweep plan
+
+struct Sweep {
+    const ParamDesc *P;   // [L+1]
+    const UpdDesc *U;     // [Q]
+    const uint32_t *B;    // [Q][ntiles+1]: first entry of update q at or after the start of tile t
+    const uint32_t *pa_off;   // [Q+1] CSR over PS time: updates pulled at that time and applied >= 2 later
+    const uint32_t *pa_list;
+    uint32_t *ovf;        // ovf[0] = number of tiles left to the slow kernel, ovf[1..] = their ids
+    uint32_t L, Q;
+    uint32_t ntiles, tile_shift;
+    float lr;
+};
+
+__device__ __forceinline__ uint32_t tile_layer(const ParamDesc *P, uint32_t L, uint32_t t) {
+    uint32_t lo = 0, hi = L;  // the last l with tile_base[l] <= t
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (P[mid].tile_base <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// B[q][t] by bisection in the sorted index list of the tile's tensor.
+__global__ __launch_bounds__(BLOCK) void k_bounds(Sweep sw, uint32_t *B) {
+    const uint64_t g = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+    const uint64_t per = (uint64_t)sw.ntiles + 1;
+    if (g >= per * sw.Q) return;
+    const uint32_t q = (uint32_t)(g / per), t = (uint32_t)(g % per);
+    const UpdDesc u = sw.U[q];
+    if (t == sw.ntiles) {
+        B[g] = (uint32_t)u.off[sw.L];
+        return;
+    }
+    const uint32_t l = tile_layer(sw.P, sw.L, t);
+    const uint32_t c0 = (t - (uint32_t)sw.P[l].tile_base) << sw.tile_shift;
+    uint64_t lo = u.off[l], hi = u.off[l + 1];
+    while (lo < hi) {
+        const uint64_t mid = lo + ((hi - lo) >> 1);
+        if (u.idx[mid] < c0) lo = mid + 1; else hi = mid;
+    }
+    B[g] = (uint32_t)lo;
+}
+
+// Exclusive prefix sum over the workgroup; `total` receives the sum.  s_wave: WAVES words.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *s_wave, uint32_t &total) {
+    const uint32_t lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    uint32_t incl = x;
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        const uint32_t y = __shfl_up(incl, d);
+        if (lane >= (uint32_t)d) incl += y;
+    }
+    if (lane == WAVE - 1) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0;
+    total = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < WAVES; ++w) {
+        const uint32_t s = s_wave[w];
+        if (w < wave) base += s;
+        total += s;
+    }
+    __syncthreads();
+    return base + incl - x;
+}
+
+// Slices of up to BLOCK consecutive updates in tile t, laid end to end: s_off[i] is the
+// position of the first entry of update q0+i (s_off[BLOCK] = number of entries), s_b0[i]
+// its entry number inside the update.  Returns the number of entries.
+__device__ __forceinline__ uint32_t load_slices(const Sweep &sw, uint32_t t, uint32_t q0, uint32_t *s_off,
+                                                uint32_t *s_b0, uint32_t *s_wave) {
+    const uint32_t q = q0 + threadIdx.x;
+    uint32_t b0 = 0, len = 0;
+    if (q < sw.Q) {
+        const uint32_t *row = sw.B + (uint64_t)q * (sw.ntiles + 1) + t;
+        b0 = row[0];
+        len = row[1] - b0;
+    }
+    uint32_t total;
+    const uint32_t o = block_exclusive_scan(len, s_wave, total);
+    s_off[threadIdx.x] = o;
+    s_b0[threadIdx.x] = b0;
+    if (threadIdx.x == 0) s_off[BLOCK] = total;
+    __syncthreads();
+    return total;
+}
+
+// Update (relative to q0) that owns staged position p: the last i with s_off[i] <= p.
+__device__ __forceinline__ uint32_t slice_of(const uint32_t *s_off, uint32_t p) {
+    uint32_t lo = 0, hi = BLOCK;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (s_off[mid] <= p) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
+    __shared__ uint32_t s_cur[TILE_MAX];     // per coordinate: count, then start, then end of its list
+    __shared__ uint32_t s_key[STAGE_CAP];    // per touch: update number | non-zero flag << 31
+    __shared__ float s_val[STAGE_CAP];
+    __shared__ uint32_t s_off[BLOCK + 1], s_b0[BLOCK], s_wave[WAVES];
+    __shared__ uint32_t s_bad;
+
+    const uint32_t t = blockIdx.x, tid = threadIdx.x;
+    const uint32_t tile = 1u << sw.tile_shift;
+    const uint32_t l = tile_layer(sw.P, sw.L, t);
+    const ParamDesc pd = sw.P[l];
+    const uint32_t c0 = (t - (uint32_t)pd.tile_base) << sw.tile_shift;
+    const uint32_t per_thread = tile / BLOCK;
+
+    for (uint32_t c = tid; c < tile; c += BLOCK) s_cur[c] = 0;
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+
+    // pass A: count the touches of every coordinate
+    uint32_t total = 0;
+    for (uint32_t q0 = 0; q0 < sw.Q; q0 += BLOCK) {
+        const uint32_t n_pass = load_slices(sw, t, q0, s_off, s_b0, s_wave);
+        total += n_pass;
+        if (total > STAGE_CAP) break;  // uniform
+        for (uint32_t p = tid; p < n_pass; p += BLOCK) {
+            const uint32_t i = slice_of(s_off, p);
+            const uint32_t e = s_b0[i] + (p - s_off[i]);
+            const uint32_t c = sw.U[q0 + i].idx[e] - c0;
+            if (c >= tile) {  // only a malformed (unsorted) index list gets here
+                s_bad = 1;
+                continue;
+            }
+            if (atomicAdd(&s_cur[c], 1u) >= LIST_MAX) s_bad = 1;
+        }
+        __syncthreads();
+    }
+    if (total > STAGE_CAP || s_bad) {  // leave the tile untouched for the slow kernel
+        if (tid == 0) sw.ovf[1 + atomicAdd(&sw.ovf[0], 1u)] = t;
+        return;
+    }
+    if (total == 0) return;
+
+    // counts -> list starts (exclusive scan, per_thread consecutive coordinates per thread)
+    {
+        uint32_t sum = 0;
+        for (uint32_t j = 0; j < per_thread; ++j) sum += s_cur[tid * per_thread + j];
+        uint32_t all;
+        uint32_t run = block_exclusive_scan(sum, s_wave, all);
+        for (uint32_t j = 0; j < per_thread; ++j) {
+            const uint32_t c = s_cur[tid * per_thread + j];
+            s_cur[tid * per_thread + j] = run;
+            run += c;
+        }
+        __syncthreads();
+    }
+
+    // pass B: group the touches by coordinate (list order is arbitrary, time is in the key)
+    for (uint32_t q0 = 0; q0 < sw.Q; q0 += BLOCK) {
+        const uint32_t n_pass = load_slices(sw, t, q0, s_off, s_b0, s_wave);
+        for (uint32_t p = tid; p < n_pass; p += BLOCK) {
+            const uint32_t i = slice_of(s_off, p);
+            const uint32_t e = s_b0[i] + (p - s_off[i]);
+            const UpdDesc &u = sw.U[q0 + i];
+            const uint32_t c = u.idx[e] - c0;
+            const float v = u.val[e];
+            const uint32_t pos = atomicAdd(&s_cur[c], 1u);
+            s_key[pos] = (q0 + i) | (is_nonzero(v) ? 0x80000000u : 0u);
+            s_val[pos] = v;
+        }
+        __syncthreads();
+    }
+
+    // replay: thread <-> coordinates tid, tid + BLOCK, ...; all loads of Theta and cnt first
+    constexpr uint32_t SLOTS = TILE_MAX / BLOCK;
+    float th[SLOTS];
+    uint32_t cn[SLOTS], beg[SLOTS], end[SLOTS];
+#pragma unroll
+    for (uint32_t s = 0; s < SLOTS; ++s) {
+        const uint32_t c = s * BLOCK + tid;
+        beg[s] = end[s] = 0;
+        if (c < tile) {
+            end[s] = s_cur[c];
+            beg[s] = c ? s_cur[c - 1] : 0u;
+        }
+        if (end[s] > beg[s]) {
+            th[s] = pd.theta[c0 + c];
+            cn[s] = pd.cnt[c0 + c];
+        }
+    }
+#pragma unroll
+    for (uint32_t s = 0; s < SLOTS; ++s) {
+        if (end[s] <= beg[s]) continue;
+        const uint32_t c = s * BLOCK + tid;
+        float theta = th[s];
+        uint32_t nonzero_touches = 0;
+        int last = -1;
+        for (uint32_t m = beg[s]; m < end[s]; ++m) {
+            // next touch in time: the smallest update number above `last`
+            uint32_t best_q = 0xffffffffu, best = beg[s];
+            for (uint32_t x = beg[s]; x < end[s]; ++x) {
+                const uint32_t q = s_key[x] & 0x7fffffffu;
+                if ((int)q > last && q < best_q) {
+                    best_q = q;
+                    best = x;
+                }
+            }
+            const uint32_t pull = sw.U[best_q].pull;
+            uint32_t sigma = 0;  // eq. 3 on this coordinate's own touches
+            for (uint32_t x = beg[s]; x < end[s]; ++x) {
+                const uint32_t k = s_key[x];
+                const uint32_t q = k & 0x7fffffffu;
+                sigma += (k >> 31) & (uint32_t)(q >= pull && q < best_q);
+            }
+            theta = step(theta, sw.lr, sigma, s_val[best]);
+            nonzero_touches += s_key[best] >> 31;
+            last = (int)best_q;
+        }
+        pd.theta[c0 + c] = theta;
+        if (nonzero_touches) pd.cnt[c0 + c] = cn[s] + nonzero_touches;
+    }
+}
+
+// Tiles the fast kernel declined: update by update from global memory, one workgroup per
+// tile, with the snapshot scheme of the scatter plan restricted to the tile.
+__global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
+    const uint32_t n_ovf = sw.ovf[0];
+    for (uint32_t o = blockIdx.x; o < n_ovf; o += gridDim.x) {
+        const uint32_t t = sw.ovf[1 + o];
+        const uint32_t l = tile_layer(sw.P, sw.L, t);
+        const ParamDesc pd = sw.P[l];
+        for (uint32_t q = 0; q < sw.Q; ++q) {
+            for (uint32_t a = sw.pa_off[q]; a < sw.pa_off[q + 1]; ++a) {
+                const UpdDesc u = sw.U[sw.pa_list[a]];
+                const uint32_t *row = sw.B + (uint64_t)sw.pa_list[a] * (sw.ntiles + 1) + t;
+                for (uint32_t e = row[0] + threadIdx.x; e < row[1]; e += BLOCK) u.snap[e] = pd.cnt[u.idx[e]];
+            }
+            __syncthreads();
+            const UpdDesc u = sw.U[q];
+            const uint32_t *row = sw.B + (uint64_t)q * (sw.ntiles + 1) + t;
+            const bool stale = q - u.pull >= 2;
+            for (uint32_t e = row[0] + threadIdx.x; e < row[1]; e += BLOCK) {
+                const uint32_t k = u.idx[e];
+                const float v = u.val[e];
+                const uint32_t c = pd.cnt[k];
+                const uint32_t sigma = stale ? c - u.snap[e] : 0u;
+                pd.theta[k] = step(pd.theta[k], sw.lr, sigma, v);
+                if (is_nonzero(v)) pd.cnt[k] = c + 1;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host side
+
 struct Layout {
-    size_t table = 0;
+    bool sweep = false;
+    uint32_t tile_shift = 0;
+    uint64_t ntiles = 0;
+    size_t table = 0, upd = 0, pa_off = 0, pa_list = 0, bounds = 0, ovf = 0;
     std::vector<size_t> snap;  // byte offset per update
     size_t bytes = 0;
 };
@@ -98,15 +399,50 @@ int check_updates(uint32_t L, const adacomp_update_t *updates, uint32_t Q) {
     return ADACOMP_OK;
 }
 
-void make_layout(uint32_t L, const adacomp_update_t *updates, uint32_t Q, Layout &lay) {
-    size_t off = 0;
-    lay.table = off;
-    off += align_up((size_t)(L ? L : 1) * sizeof(ParamDesc), 256);
-    lay.snap.resize(Q);
+// Plan and workspace layout from sizes alone.  The sweep pays 16 bytes per parameter plus
+// about 30 per entry; the scatter about 440 bytes per entry (measured line traffic).
+void make_layout(const uint64_t *n, uint32_t L, const adacomp_update_t *updates, uint32_t Q, Layout &lay) {
+    double entries = 0, params = 0;
+    bool fits32 = true;
     for (uint32_t q = 0; q < Q; ++q) {
-        lay.snap[q] = off;
-        off += align_up((size_t)updates[q].layer_off[L] * sizeof(uint32_t) + 1, 256);
+        entries += (double)updates[q].layer_off[L];
+        fits32 = fits32 && updates[q].layer_off[L] <= 0xffffffffull;
     }
+    for (uint32_t l = 0; l < L; ++l) params += (double)n[l];
+    // ADACOMP_APPLY_PLAN=scatter|sweep overrides the cost model (for tests and measurements)
+    const char *force = std::getenv("ADACOMP_APPLY_PLAN");
+    const bool never = force && std::strcmp(force, "scatter") == 0;
+    const bool always = force && std::strcmp(force, "sweep") == 0;
+    if (!never && Q >= 2 && Q <= (1u << 20) && fits32 && L > 0 && params > 0 && entries > 0) {
+        // tile: about STAGE_CAP / 2 queued entries per tile on average
+        const double per_coord = entries / params;
+        uint32_t shift = 12;  // TILE_MAX
+        while ((1u << shift) > BLOCK && (double)(1u << shift) * per_coord > STAGE_CAP / 2) --shift;
+        uint64_t ntiles = 0;
+        for (uint32_t l = 0; l < L; ++l) ntiles += (n[l] + (1ull << shift) - 1) >> shift;
+        const double sweep_cost = 1.25 * (16.0 * params + 30.0 * entries + 8.0 * (double)Q * (double)ntiles);
+        if (ntiles < 0x7fffffffull && (always || 440.0 * entries > sweep_cost)) {
+            lay.sweep = true;
+            lay.tile_shift = shift;
+            lay.ntiles = ntiles;
+        }
+    }
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += align_up(bytes ? bytes : 1, 256);
+        return at;
+    };
+    lay.table = take(((size_t)L + 1) * sizeof(ParamDesc));
+    if (lay.sweep) {
+        lay.upd = take((size_t)Q * sizeof(UpdDesc));
+        lay.pa_off = take(((size_t)Q + 1) * sizeof(uint32_t));
+        lay.pa_list = take((size_t)Q * sizeof(uint32_t));
+        lay.bounds = take((size_t)Q * (lay.ntiles + 1) * sizeof(uint32_t));
+        lay.ovf = take((lay.ntiles + 1) * sizeof(uint32_t));
+    }
+    lay.snap.resize(Q);
+    for (uint32_t q = 0; q < Q; ++q) lay.snap[q] = take((size_t)updates[q].layer_off[L] * sizeof(uint32_t));
     lay.bytes = off;
 }
 
@@ -115,16 +451,21 @@ void make_layout(uint32_t L, const adacomp_update_t *updates, uint32_t Q, Layout
 
 using namespace adacomp;
 
-extern "C" int adacomp_apply_workspace(uint32_t L, const adacomp_update_t *updates, uint32_t Q,
-                                       size_t *bytes) {
-    if (!bytes) return ADACOMP_ERR_NULL;
+extern "C" int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
+                                       uint32_t Q, size_t *bytes) {
+    if (!bytes || (L && !n)) return ADACOMP_ERR_NULL;
     int rc = check_updates(L, updates, Q);
     if (rc) return rc;
     Layout lay;
-    make_layout(L, updates, Q, lay);
+    make_layout(n, L, updates, Q, lay);
     *bytes = lay.bytes;
     return ADACOMP_OK;
 }
+
+#define CHECK_LAUNCH()                                               \
+    do {                                                             \
+        if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP; \
+    } while (0)
 
 extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, adacomp_state_t *st,
                              const adacomp_update_t *updates, uint32_t Q, float lr,
@@ -134,13 +475,16 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
     if (!std::isfinite(lr)) return ADACOMP_ERR_LR;
     int rc = check_updates(L, updates, Q);
     if (rc) return rc;
-    std::vector<ParamDesc> table(L);
+    std::vector<ParamDesc> table((size_t)L + 1);
+    std::vector<uint64_t> n(L);
     for (uint32_t l = 0; l < L; ++l) {
         if (params[l].n > 0xffffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
         if (params[l].n && (!params[l].data || !st->cnt[l])) return ADACOMP_ERR_NULL;
         if (((uintptr_t)params[l].data & 3u) || ((uintptr_t)st->cnt[l] & 3u)) return ADACOMP_ERR_ALIGNMENT;
-        table[l] = ParamDesc{params[l].data, st->cnt[l], params[l].n};
+        table[l] = ParamDesc{params[l].data, st->cnt[l], params[l].n, 0};
+        n[l] = params[l].n;
     }
+    table[L] = ParamDesc{nullptr, nullptr, 0, 0};
     const uint64_t t0 = st->t;
     for (uint32_t q = 0; q < Q; ++q) {
         const adacomp_update_t &u = updates[q];
@@ -155,15 +499,13 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         if (u.pull_ts < t0) return ADACOMP_ERR_HISTORY;
     }
     Layout lay;
-    make_layout(L, updates, Q, lay);
+    make_layout(n.data(), L, updates, Q, lay);
     if (!workspace || ((uintptr_t)workspace & 255u) || ws_bytes < lay.bytes) return ADACOMP_ERR_WORKSPACE;
     if (Q == 0) return ADACOMP_OK;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     char *wsb = static_cast<char *>(workspace);
     ParamDesc *P = reinterpret_cast<ParamDesc *>(wsb + lay.table);
-    if (L && put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess)
-        return ADACOMP_ERR_HIP;
 
     // pulled_at[q]: updates whose worker pulled at PS time t0 + q and that arrive two
     // or more iterations later (Alg. 1 "Pull" / Alg. 2 "Get"): their counters are
@@ -177,6 +519,59 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
             pulled_at[j].push_back(q);
         }
     }
+
+    if (lay.sweep) {
+        uint64_t tiles = 0;
+        for (uint32_t l = 0; l < L; ++l) {
+            table[l].tile_base = tiles;
+            tiles += (n[l] + (1ull << lay.tile_shift) - 1) >> lay.tile_shift;
+        }
+        table[L].tile_base = tiles;
+        std::vector<UpdDesc> upd(Q);
+        std::vector<uint32_t> pa_off((size_t)Q + 1, 0), pa_list;
+        for (uint32_t q = 0; q < Q; ++q) {
+            const adacomp_update_t &u = updates[q];
+            upd[q] = UpdDesc{u.idx, u.val, u.layer_off_dev, reinterpret_cast<uint32_t *>(wsb + lay.snap[q]),
+                             (uint32_t)(u.pull_ts - t0), 0};
+            pa_off[q] = (uint32_t)pa_list.size();
+            pa_list.insert(pa_list.end(), pulled_at[q].begin(), pulled_at[q].end());
+        }
+        pa_off[Q] = (uint32_t)pa_list.size();
+        pa_list.resize(Q, 0);
+        Sweep sw;
+        sw.P = P;
+        sw.U = reinterpret_cast<const UpdDesc *>(wsb + lay.upd);
+        sw.B = reinterpret_cast<const uint32_t *>(wsb + lay.bounds);
+        sw.pa_off = reinterpret_cast<const uint32_t *>(wsb + lay.pa_off);
+        sw.pa_list = reinterpret_cast<const uint32_t *>(wsb + lay.pa_list);
+        sw.ovf = reinterpret_cast<uint32_t *>(wsb + lay.ovf);
+        sw.L = L;
+        sw.Q = Q;
+        sw.ntiles = (uint32_t)lay.ntiles;
+        sw.tile_shift = lay.tile_shift;
+        sw.lr = lr;
+        if (put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess ||
+            put_async(wsb + lay.upd, upd.data(), upd.size() * sizeof(UpdDesc), s) != hipSuccess ||
+            put_async(wsb + lay.pa_off, pa_off.data(), pa_off.size() * sizeof(uint32_t), s) != hipSuccess ||
+            put_async(wsb + lay.pa_list, pa_list.data(), pa_list.size() * sizeof(uint32_t), s) != hipSuccess ||
+            fill_u32_async(sw.ovf, 0u, 1, s) != hipSuccess)
+            return ADACOMP_ERR_HIP;
+        const uint64_t nb = ((uint64_t)Q * (lay.ntiles + 1) + BLOCK - 1) / BLOCK;
+        if (nb > 0x7fffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_BOUNDS, k_bounds, dim3((unsigned)nb), dim3(BLOCK), s, sw,
+                       reinterpret_cast<uint32_t *>(wsb + lay.bounds));
+        CHECK_LAUNCH();
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep, dim3((unsigned)lay.ntiles), dim3(BLOCK), s, sw);
+        CHECK_LAUNCH();
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP_SLOW, k_sweep_slow,
+                       dim3((unsigned)std::min<uint64_t>(lay.ntiles, SLOW_GRID)), dim3(BLOCK), s, sw);
+        CHECK_LAUNCH();
+        st->t = t0 + Q;
+        return ADACOMP_OK;
+    }
+
+    if (L && put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess)
+        return ADACOMP_ERR_HIP;
     for (uint32_t q = 0; q < Q; ++q) {
         for (uint32_t w : pulled_at[q]) {
             const adacomp_update_t &u = updates[w];
@@ -184,7 +579,7 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
             const unsigned grid = (unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS));
             ADACOMP_LAUNCH(ADACOMP_KERNEL_SNAPSHOT, k_snapshot, dim3(grid), dim3(BLOCK), s, P, L,
                            u.layer_off_dev, u.idx, reinterpret_cast<uint32_t *>(wsb + lay.snap[w]), total);
-            if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
+            CHECK_LAUNCH();
         }
         const adacomp_update_t &u = updates[q];
         const uint64_t total = u.layer_off[L];
@@ -197,7 +592,7 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         else
             ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, k_scatter_apply<false>, dim3(grid), dim3(BLOCK), s, P, L,
                            u.layer_off_dev, u.idx, u.val, snap, total, lr);
-        if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
+        CHECK_LAUNCH();
     }
     st->t = t0 + Q;
     return ADACOMP_OK;

@@ -93,6 +93,9 @@ extern "C" const char *adacomp_kernel_name(int id) {
         case ADACOMP_KERNEL_IDENTITY: return "identity";
         case ADACOMP_KERNEL_SNAPSHOT: return "snapshot";
         case ADACOMP_KERNEL_SCATTER_APPLY: return "scatter_apply";
+        case ADACOMP_KERNEL_BOUNDS: return "bounds";
+        case ADACOMP_KERNEL_SWEEP: return "sweep";
+        case ADACOMP_KERNEL_SWEEP_SLOW: return "sweep_slow";
         default: return "?";
     }
 }

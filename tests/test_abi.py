@@ -127,4 +127,5 @@ def test_apply_argument_checks_run_before_any_launch(lib):
     st.num_layers = 1
     assert st.t == 5                                        # no failing call advanced the timestamp
     need = C.c_size_t()
-    assert lib.adacomp_apply_workspace(1, upd, 1, C.byref(need)) == 0 and need.value >= 12
+    n = (C.c_uint64 * 1)(100)
+    assert lib.adacomp_apply_workspace(n, 1, upd, 1, C.byref(need)) == 0 and need.value >= 12

@@ -39,7 +39,7 @@ def run_gpu(ac, theta_host, updates_host, pulls, lr, dev, chunks=None, state=Non
     pos = 0
     for c in chunks:
         part = ups[pos:pos + c]
-        ws = torch.empty(max(ac.adacomp_apply_workspace(L, part), 256), dtype=torch.uint8, device=dev)
+        ws = torch.empty(max(ac.adacomp_apply_workspace([t.numel() for t in theta], part), 256), dtype=torch.uint8, device=dev)
         ac.adacomp_apply(theta, st, part, lr, ws)
         pos += c
     torch.cuda.synchronize()
@@ -252,7 +252,7 @@ def test_flat_config_full_size_sampled(ac, dev):
         ups.append(gpu_select(ac, g, rate, pull_ts=pulls[q], ws=ws))
         del g
     st = ac.State(theta)
-    aws = torch.empty(ac.adacomp_apply_workspace(L, ups), dtype=torch.uint8, device=dev)
+    aws = torch.empty(ac.adacomp_apply_workspace(sizes, ups), dtype=torch.uint8, device=dev)
     print("[apply] flat: gpu apply", flush=True)
     ac.adacomp_apply(theta, st, ups, lr, aws)
     torch.cuda.synchronize()
@@ -269,3 +269,72 @@ def test_flat_config_full_size_sampled(ac, dev):
         o_ups = oracle_select_parallel([[x] for x in host_g[l]], rate, threads=8)
         want = run_oracle([theta0[l]], o_ups, pulls, lr)
         assert compare([theta[l].cpu().numpy()], want, f"flat tensor {l}") == 0
+
+
+@pytest.mark.parametrize("plan", ["scatter", "sweep"])
+def test_both_plans_on_the_same_queues(ac, dev, plan, monkeypatch):
+    """The execution plan is an internal choice; forced either way the result is the oracle's.
+    Includes queues that overflow a tile's LDS lists (hot coordinates, dense updates), which the
+    sweep hands to its per-tile fallback kernel."""
+    monkeypatch.setenv("ADACOMP_APPLY_PLAN", plan)
+    rng = np.random.default_rng(2024)
+    cases = []
+    # sparse, many tensors, ragged sizes, several tiles per tensor
+    sizes = [70_001, 5, 0, 12_345, 1, 300_000]
+    cases.append(("sparse", sizes, random_updates(rng, sizes, 40, 0.01, zero_frac=0.05)))
+    # dense: every update touches 60% of every tensor -> tiles overflow the stage
+    sizes = [5_000, 777]
+    cases.append(("dense", sizes, random_updates(rng, sizes, 30, 0.6)))
+    # hot coordinates: 400 updates all hitting the same few parameters -> lists beyond LIST_MAX
+    sizes = [10_000, 3]
+    hot = []
+    for q in range(400):
+        i0 = np.unique(np.concatenate([[7, 4099, 9999], rng.integers(0, 10_000, 20)])).astype(np.uint32)
+        i1 = np.array([0, 2], dtype=np.uint32)
+        v = rng.standard_normal(i0.size + 2).astype(np.float32)
+        hot.append((np.array([0, i0.size, i0.size + 2], dtype=np.uint64), np.concatenate([i0, i1]), v))
+    cases.append(("hot", sizes, hot))
+    for name, sizes, ups in cases:
+        Q = len(ups)
+        pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+        theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+        got, cnt, st = run_gpu(ac, theta0, ups, pulls, 0.03, dev)
+        want = run_oracle(theta0, ups, pulls, 0.03)
+        assert st.t == Q
+        assert compare(got, want, f"{plan}/{name}") == 0
+        for l, n in enumerate(sizes):
+            ref = np.zeros(max(n, 1), dtype=np.int64)
+            for o, i, v in ups:
+                sl = slice(int(o[l]), int(o[l + 1]))
+                np.add.at(ref, i[sl][v[sl] != 0], 1)
+            assert np.array_equal(cnt[l].astype(np.int64), ref), f"{plan}/{name} counters tensor {l}"
+
+
+def test_sweep_and_scatter_agree_on_cnn_queue_bitwise(ac, dev, monkeypatch):
+    """Same seeded queue (updates built with torch.topk here, not by either implementation under
+    test), both plans: identical parameters and counters."""
+    cfg = "cnn_apply"
+    sizes = workloads.sizes_of(cfg)
+    Q = 40
+    pulls = workloads.pull_timestamps(workloads.staleness(cfg, Q))
+    ups = []
+    for q in range(Q):
+        off, idx, val = [0], [], []
+        for g in workloads.gradient(cfg, q, device=dev):
+            k = max(1, g.numel() // 100)
+            i = torch.topk(g.abs(), k).indices.sort().values
+            idx.append(i.cpu().numpy().astype(np.uint32))
+            val.append(g[i].cpu().numpy())
+            off.append(off[-1] + k)
+        ups.append((np.array(off, dtype=np.uint64), np.concatenate(idx), np.concatenate(val)))
+    theta0 = [t.numpy() for t in workloads.theta0(cfg)]
+    res = {}
+    for plan in ("scatter", "sweep"):
+        monkeypatch.setenv("ADACOMP_APPLY_PLAN", plan)
+        res[plan] = run_gpu(ac, theta0, ups, pulls, 0.01, dev)
+    for a, b in zip(res["scatter"][0], res["sweep"][0]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    for a, b in zip(res["scatter"][1], res["sweep"][1]):
+        assert np.array_equal(a, b)
+    want = run_oracle(theta0, ups, pulls, 0.01, method=oracle.HISTORY_BITMAP)
+    assert compare(res["sweep"][0], want, "cnn queue, sweep") == 0
