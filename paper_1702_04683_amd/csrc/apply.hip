@@ -38,10 +38,13 @@ namespace {
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t WAVES = BLOCK / WAVE;
 constexpr uint32_t ITEMS = 4;          // scatter plan: entries per thread
-constexpr uint32_t TILE_MAX = 4096;    // sweep plan: coordinates per tile (power of two, >= BLOCK)
-constexpr uint32_t STAGE_CAP = 2048;   // sweep plan: entries of the whole queue a tile can hold in LDS
+constexpr uint32_t TILE_MAX = 2048;    // sweep plan: coordinates per tile (power of two, >= BLOCK)
+constexpr uint32_t STAGE_CAP = 512;    // sweep plan: entries of the whole queue a tile can hold in LDS
 constexpr uint32_t LIST_MAX = 128;     // sweep plan: touches of one coordinate the fast kernel replays
 constexpr uint32_t SLOW_GRID = 1024;
+constexpr uint32_t PASS = 256;           // sweep plan: updates whose slices are staged together
+static_assert((TILE_MAX & (TILE_MAX - 1)) == 0 && TILE_MAX >= BLOCK && STAGE_CAP % BLOCK == 0 && STAGE_CAP <= 65535,
+              "tile and stage sizes");
 
 struct ParamDesc {
     float *theta;
@@ -130,6 +133,7 @@ struct Sweep {
     const ParamDesc *P;   // [L+1]
     const UpdDesc *U;     // [Q]
     const uint32_t *B;    // [Q][ntiles+1]: first entry of update q at or after the start of tile t
+    const uint32_t *tile_tensor;  // [ntiles] tensor that owns tile t
     const uint32_t *pa_off;   // [Q+1] CSR over PS time: updates pulled at that time and applied >= 2 later
     const uint32_t *pa_list;
     uint32_t *ovf;        // ovf[0] = number of tiles left to the slow kernel, ovf[1..] = their ids
@@ -147,8 +151,8 @@ __device__ __forceinline__ uint32_t tile_layer(const ParamDesc *P, uint32_t L, u
     return lo;
 }
 
-// B[q][t] by bisection in the sorted index list of the tile's tensor.
-__global__ __launch_bounds__(BLOCK) void k_bounds(Sweep sw, uint32_t *B) {
+// B[q][t] by bisection in the sorted index list of the tile's tensor; tile_tensor[t].
+__global__ __launch_bounds__(BLOCK) void k_bounds(Sweep sw, uint32_t *B, uint32_t *tile_tensor) {
     const uint64_t g = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
     const uint64_t per = (uint64_t)sw.ntiles + 1;
     if (g >= per * sw.Q) return;
@@ -159,6 +163,7 @@ __global__ __launch_bounds__(BLOCK) void k_bounds(Sweep sw, uint32_t *B) {
         return;
     }
     const uint32_t l = tile_layer(sw.P, sw.L, t);
+    if (q == 0) tile_tensor[t] = l;
     const uint32_t c0 = (t - (uint32_t)sw.P[l].tile_base) << sw.tile_shift;
     uint64_t lo = u.off[l], hi = u.off[l + 1];
     while (lo < hi) {
@@ -191,70 +196,104 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *s
     return base + incl - x;
 }
 
-// Slices of up to BLOCK consecutive updates in tile t, laid end to end: s_off[i] is the
-// position of the first entry of update q0+i (s_off[BLOCK] = number of entries), s_b0[i]
-// its entry number inside the update.  Returns the number of entries.
-__device__ __forceinline__ uint32_t load_slices(const Sweep &sw, uint32_t t, uint32_t q0, uint32_t *s_off,
-                                                uint32_t *s_b0, uint32_t *s_wave) {
+// Slices of up to PASS consecutive updates (q0 ..) inside tile t, laid end to end.
+struct Slices {
+    uint32_t off[PASS + 1];      // position of the first entry of update q0+i; off[n] = entries
+    uint32_t b0[PASS];           // its entry number inside the update
+    const uint32_t *idx[PASS];   // the update's arrays
+    const float *val[PASS];
+    uint32_t tag[PASS];          // update number | staleness << 15 (key bits of its touches)
+};
+
+__device__ __forceinline__ uint32_t load_slices(const Sweep &sw, uint32_t t, uint32_t q0, Slices &sl,
+                                                uint32_t *s_wave) {
     const uint32_t q = q0 + threadIdx.x;
+    const bool mine = threadIdx.x < PASS && q < sw.Q;
     uint32_t b0 = 0, len = 0;
-    if (q < sw.Q) {
+    if (mine) {
         const uint32_t *row = sw.B + (uint64_t)q * (sw.ntiles + 1) + t;
+        const UpdDesc u = sw.U[q];
         b0 = row[0];
         len = row[1] - b0;
+        sl.idx[threadIdx.x] = u.idx;
+        sl.val[threadIdx.x] = u.val;
+        sl.tag[threadIdx.x] = q | ((q - u.pull) << 15);
     }
     uint32_t total;
     const uint32_t o = block_exclusive_scan(len, s_wave, total);
-    s_off[threadIdx.x] = o;
-    s_b0[threadIdx.x] = b0;
-    if (threadIdx.x == 0) s_off[BLOCK] = total;
+    if (threadIdx.x <= PASS) sl.off[threadIdx.x] = o;  // off[n_slices .. PASS] = total
+    if (mine) sl.b0[threadIdx.x] = b0;
     __syncthreads();
     return total;
 }
 
-// Update (relative to q0) that owns staged position p: the last i with s_off[i] <= p.
-__device__ __forceinline__ uint32_t slice_of(const uint32_t *s_off, uint32_t p) {
-    uint32_t lo = 0, hi = BLOCK;
+// Update (relative to q0) that owns staged position p: the last i with off[i] <= p.
+__device__ __forceinline__ uint32_t slice_of(const uint32_t *off, uint32_t n_slices, uint32_t p) {
+    uint32_t lo = 0, hi = n_slices;
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
-        if (s_off[mid] <= p) lo = mid; else hi = mid;
+        if (off[mid] <= p) lo = mid; else hi = mid;
     }
     return lo;
 }
 
+constexpr uint32_t PER_THREAD = STAGE_CAP / BLOCK;  // staged entries per thread and pass
+
+__device__ __forceinline__ uint32_t slot(uint32_t c) { return c + (c >> 4); }
+
+// A touch in LDS: key = update number (15 bits) | its global staleness q - pull (15 bits,
+// from bit 15) | value-is-non-zero (bit 31); value separately.
 __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
-    __shared__ uint32_t s_cur[TILE_MAX];     // per coordinate: count, then start, then end of its list
-    __shared__ uint32_t s_key[STAGE_CAP];    // per touch: update number | non-zero flag << 31
+    // per coordinate: count, then start, then end of its list; slot(c) skews the index so
+    // that the scan's 16-consecutive-per-thread accesses fall into distinct banks
+    __shared__ uint32_t s_cur[TILE_MAX + TILE_MAX / 16];
+    __shared__ uint32_t s_key[STAGE_CAP];
     __shared__ float s_val[STAGE_CAP];
-    __shared__ uint32_t s_off[BLOCK + 1], s_b0[BLOCK], s_wave[WAVES];
+    __shared__ float s_prod[STAGE_CAP];      // alpha_k * value of every touch, per coordinate in time order
+    __shared__ uint16_t s_coord[STAGE_CAP];  // coordinate (inside the tile) of every touch
+    __shared__ Slices sl;
+    __shared__ uint32_t s_wave[WAVES];
     __shared__ uint32_t s_bad;
 
     const uint32_t t = blockIdx.x, tid = threadIdx.x;
     const uint32_t tile = 1u << sw.tile_shift;
-    const uint32_t l = tile_layer(sw.P, sw.L, t);
-    const ParamDesc pd = sw.P[l];
+    const ParamDesc pd = sw.P[sw.tile_tensor[t]];
     const uint32_t c0 = (t - (uint32_t)pd.tile_base) << sw.tile_shift;
     const uint32_t per_thread = tile / BLOCK;
 
-    for (uint32_t c = tid; c < tile; c += BLOCK) s_cur[c] = 0;
+    const uint32_t ncoord = pd.n - c0 < tile ? (uint32_t)(pd.n - c0) : tile;
+
+    for (uint32_t c = tid; c < tile + tile / 16; c += BLOCK) s_cur[c] = 0;
     if (tid == 0) s_bad = 0;
     __syncthreads();
 
-    // pass A: count the touches of every coordinate
+    // pass A: count the touches of every coordinate.  With a queue of at most PASS updates
+    // there is one pass and the entries stay in registers for pass B.
+    uint32_t c[PER_THREAD], key[PER_THREAD];
+    float v[PER_THREAD];
     uint32_t total = 0;
-    for (uint32_t q0 = 0; q0 < sw.Q; q0 += BLOCK) {
-        const uint32_t n_pass = load_slices(sw, t, q0, s_off, s_b0, s_wave);
+    for (uint32_t q0 = 0; q0 < sw.Q; q0 += PASS) {
+        const uint32_t n_pass = load_slices(sw, t, q0, sl, s_wave);
+        const uint32_t n_slices = sw.Q - q0 < PASS ? sw.Q - q0 : PASS;
         total += n_pass;
         if (total > STAGE_CAP) break;  // uniform
-        for (uint32_t p = tid; p < n_pass; p += BLOCK) {
-            const uint32_t i = slice_of(s_off, p);
-            const uint32_t e = s_b0[i] + (p - s_off[i]);
-            const uint32_t c = sw.U[q0 + i].idx[e] - c0;
-            if (c >= tile) {  // only a malformed (unsorted) index list gets here
-                s_bad = 1;
-                continue;
+#pragma unroll
+        for (uint32_t j = 0; j < PER_THREAD; ++j) {  // all loads in flight together
+            const uint32_t p = tid + j * BLOCK;
+            c[j] = 0xffffffffu;
+            if (p < n_pass) {
+                const uint32_t i = slice_of(sl.off, n_slices, p);
+                const uint32_t e = sl.b0[i] + (p - sl.off[i]);
+                c[j] = sl.idx[i][e] - c0;
+                v[j] = sl.val[i][e];
+                key[j] = sl.tag[i];
             }
-            if (atomicAdd(&s_cur[c], 1u) >= LIST_MAX) s_bad = 1;
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < PER_THREAD; ++j) {
+            if (tid + j * BLOCK >= n_pass) continue;
+            if (c[j] >= ncoord) s_bad = 1;  // only a malformed (unsorted) index list gets here
+            else if (atomicAdd(&s_cur[slot(c[j])], 1u) >= LIST_MAX) s_bad = 1;
         }
         __syncthreads();
     }
@@ -267,80 +306,93 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
     // counts -> list starts (exclusive scan, per_thread consecutive coordinates per thread)
     {
         uint32_t sum = 0;
-        for (uint32_t j = 0; j < per_thread; ++j) sum += s_cur[tid * per_thread + j];
+        for (uint32_t j = 0; j < per_thread; ++j) sum += s_cur[slot(tid * per_thread + j)];
         uint32_t all;
         uint32_t run = block_exclusive_scan(sum, s_wave, all);
         for (uint32_t j = 0; j < per_thread; ++j) {
-            const uint32_t c = s_cur[tid * per_thread + j];
-            s_cur[tid * per_thread + j] = run;
-            run += c;
+            const uint32_t n_touch = s_cur[slot(tid * per_thread + j)];
+            s_cur[slot(tid * per_thread + j)] = run;
+            run += n_touch;
         }
         __syncthreads();
     }
 
     // pass B: group the touches by coordinate (list order is arbitrary, time is in the key)
-    for (uint32_t q0 = 0; q0 < sw.Q; q0 += BLOCK) {
-        const uint32_t n_pass = load_slices(sw, t, q0, s_off, s_b0, s_wave);
-        for (uint32_t p = tid; p < n_pass; p += BLOCK) {
-            const uint32_t i = slice_of(s_off, p);
-            const uint32_t e = s_b0[i] + (p - s_off[i]);
-            const UpdDesc &u = sw.U[q0 + i];
-            const uint32_t c = u.idx[e] - c0;
-            const float v = u.val[e];
-            const uint32_t pos = atomicAdd(&s_cur[c], 1u);
-            s_key[pos] = (q0 + i) | (is_nonzero(v) ? 0x80000000u : 0u);
-            s_val[pos] = v;
+    for (uint32_t q0 = 0; q0 < sw.Q; q0 += PASS) {
+        uint32_t n_pass = total;
+        if (sw.Q > PASS) {  // several passes: fetch this pass's entries again (cache hits)
+            n_pass = load_slices(sw, t, q0, sl, s_wave);
+            const uint32_t n_slices = sw.Q - q0 < PASS ? sw.Q - q0 : PASS;
+#pragma unroll
+            for (uint32_t j = 0; j < PER_THREAD; ++j) {
+                const uint32_t p = tid + j * BLOCK;
+                if (p < n_pass) {
+                    const uint32_t i = slice_of(sl.off, n_slices, p);
+                    const uint32_t e = sl.b0[i] + (p - sl.off[i]);
+                    c[j] = sl.idx[i][e] - c0;
+                    v[j] = sl.val[i][e];
+                    key[j] = sl.tag[i];
+                }
+            }
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < PER_THREAD; ++j) {
+            if (tid + j * BLOCK >= n_pass) continue;
+            const uint32_t pos = atomicAdd(&s_cur[slot(c[j])], 1u);
+            s_key[pos] = key[j] | (is_nonzero(v[j]) ? 0x80000000u : 0u);
+            s_val[pos] = v[j];
+            s_coord[pos] = (uint16_t)c[j];
         }
         __syncthreads();
     }
 
-    // replay: thread <-> coordinates tid, tid + BLOCK, ...; all loads of Theta and cnt first
-    constexpr uint32_t SLOTS = TILE_MAX / BLOCK;
-    float th[SLOTS];
-    uint32_t cn[SLOTS], beg[SLOTS], end[SLOTS];
+    // per touch (dense over the lists, PER_THREAD touches per thread): its rank in time among
+    // the touches of its coordinate, its staleness sigma (eq. 3 on the coordinate's own list),
+    // and the product alpha_k * value (eq. 5 and the multiply of eq. 4), stored in time order.
+    // The earliest touch of a coordinate also fetches Theta_k and cnt_k and will fold the list.
+    float theta[PER_THREAD];
+    uint32_t count[PER_THREAD], lo[PER_THREAD], hi[PER_THREAD], coord[PER_THREAD];
 #pragma unroll
-    for (uint32_t s = 0; s < SLOTS; ++s) {
-        const uint32_t c = s * BLOCK + tid;
-        beg[s] = end[s] = 0;
-        if (c < tile) {
-            end[s] = s_cur[c];
-            beg[s] = c ? s_cur[c - 1] : 0u;
+    for (uint32_t j = 0; j < PER_THREAD; ++j) {
+        const uint32_t x = tid + j * BLOCK;
+        lo[j] = hi[j] = 0;
+        if (x >= total) continue;
+        const uint32_t kx = s_key[x], cx = s_coord[x];
+        const uint32_t qx = kx & 0x7fffu;
+        const uint32_t pull = qx - ((kx >> 15) & 0x7fffu);
+        const uint32_t beg = cx ? s_cur[slot(cx - 1)] : 0u, end = s_cur[slot(cx)];
+        uint32_t rank = 0, sigma = 0;
+        for (uint32_t y = beg; y < end; ++y) {
+            const uint32_t ky = s_key[y];
+            const uint32_t qy = ky & 0x7fffu;
+            rank += qy < qx;
+            sigma += (ky >> 31) & (uint32_t)(qy >= pull && qy < qx);
         }
-        if (end[s] > beg[s]) {
-            th[s] = pd.theta[c0 + c];
-            cn[s] = pd.cnt[c0 + c];
+        float alpha = sw.lr;
+        if (sigma != 0) alpha = __fdiv_rn(sw.lr, (float)sigma);
+        s_prod[beg + rank] = __fmul_rn(alpha, s_val[x]);
+        if (rank == 0) {
+            lo[j] = beg;
+            hi[j] = end;
+            coord[j] = cx;
+            theta[j] = pd.theta[c0 + cx];
+            count[j] = pd.cnt[c0 + cx];
         }
     }
+    __syncthreads();
+
+    // per coordinate: subtract its products in time order (eq. 4), count its non-zero touches
 #pragma unroll
-    for (uint32_t s = 0; s < SLOTS; ++s) {
-        if (end[s] <= beg[s]) continue;
-        const uint32_t c = s * BLOCK + tid;
-        float theta = th[s];
+    for (uint32_t j = 0; j < PER_THREAD; ++j) {
+        if (hi[j] <= lo[j]) continue;
+        float th = theta[j];
         uint32_t nonzero_touches = 0;
-        int last = -1;
-        for (uint32_t m = beg[s]; m < end[s]; ++m) {
-            // next touch in time: the smallest update number above `last`
-            uint32_t best_q = 0xffffffffu, best = beg[s];
-            for (uint32_t x = beg[s]; x < end[s]; ++x) {
-                const uint32_t q = s_key[x] & 0x7fffffffu;
-                if ((int)q > last && q < best_q) {
-                    best_q = q;
-                    best = x;
-                }
-            }
-            const uint32_t pull = sw.U[best_q].pull;
-            uint32_t sigma = 0;  // eq. 3 on this coordinate's own touches
-            for (uint32_t x = beg[s]; x < end[s]; ++x) {
-                const uint32_t k = s_key[x];
-                const uint32_t q = k & 0x7fffffffu;
-                sigma += (k >> 31) & (uint32_t)(q >= pull && q < best_q);
-            }
-            theta = step(theta, sw.lr, sigma, s_val[best]);
-            nonzero_touches += s_key[best] >> 31;
-            last = (int)best_q;
+        for (uint32_t m = lo[j]; m < hi[j]; ++m) {
+            th = __fsub_rn(th, s_prod[m]);
+            nonzero_touches += s_key[m] >> 31;
         }
-        pd.theta[c0 + c] = theta;
-        if (nonzero_touches) pd.cnt[c0 + c] = cn[s] + nonzero_touches;
+        pd.theta[c0 + coord[j]] = th;
+        if (nonzero_touches) pd.cnt[c0 + coord[j]] = count[j] + nonzero_touches;
     }
 }
 
@@ -350,8 +402,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
     const uint32_t n_ovf = sw.ovf[0];
     for (uint32_t o = blockIdx.x; o < n_ovf; o += gridDim.x) {
         const uint32_t t = sw.ovf[1 + o];
-        const uint32_t l = tile_layer(sw.P, sw.L, t);
-        const ParamDesc pd = sw.P[l];
+        const ParamDesc pd = sw.P[sw.tile_tensor[t]];
         for (uint32_t q = 0; q < sw.Q; ++q) {
             for (uint32_t a = sw.pa_off[q]; a < sw.pa_off[q + 1]; ++a) {
                 const UpdDesc u = sw.U[sw.pa_list[a]];
@@ -381,7 +432,7 @@ struct Layout {
     bool sweep = false;
     uint32_t tile_shift = 0;
     uint64_t ntiles = 0;
-    size_t table = 0, upd = 0, pa_off = 0, pa_list = 0, bounds = 0, ovf = 0;
+    size_t table = 0, upd = 0, pa_off = 0, pa_list = 0, bounds = 0, tile_tensor = 0, ovf = 0;
     std::vector<size_t> snap;  // byte offset per update
     size_t bytes = 0;
 };
@@ -413,10 +464,11 @@ void make_layout(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
     const char *force = std::getenv("ADACOMP_APPLY_PLAN");
     const bool never = force && std::strcmp(force, "scatter") == 0;
     const bool always = force && std::strcmp(force, "sweep") == 0;
-    if (!never && Q >= 2 && Q <= (1u << 20) && fits32 && L > 0 && params > 0 && entries > 0) {
+    if (!never && Q >= 2 && Q <= 0x7fffu && fits32 && L > 0 && params > 0 && entries > 0) {
         // tile: about STAGE_CAP / 2 queued entries per tile on average
         const double per_coord = entries / params;
-        uint32_t shift = 12;  // TILE_MAX
+        uint32_t shift = 0;
+        while ((2u << shift) <= TILE_MAX) ++shift;  // log2(TILE_MAX)
         while ((1u << shift) > BLOCK && (double)(1u << shift) * per_coord > STAGE_CAP / 2) --shift;
         uint64_t ntiles = 0;
         for (uint32_t l = 0; l < L; ++l) ntiles += (n[l] + (1ull << shift) - 1) >> shift;
@@ -439,6 +491,7 @@ void make_layout(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
         lay.pa_off = take(((size_t)Q + 1) * sizeof(uint32_t));
         lay.pa_list = take((size_t)Q * sizeof(uint32_t));
         lay.bounds = take((size_t)Q * (lay.ntiles + 1) * sizeof(uint32_t));
+        lay.tile_tensor = take(lay.ntiles * sizeof(uint32_t));
         lay.ovf = take((lay.ntiles + 1) * sizeof(uint32_t));
     }
     lay.snap.resize(Q);
@@ -542,6 +595,7 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         sw.P = P;
         sw.U = reinterpret_cast<const UpdDesc *>(wsb + lay.upd);
         sw.B = reinterpret_cast<const uint32_t *>(wsb + lay.bounds);
+        sw.tile_tensor = reinterpret_cast<const uint32_t *>(wsb + lay.tile_tensor);
         sw.pa_off = reinterpret_cast<const uint32_t *>(wsb + lay.pa_off);
         sw.pa_list = reinterpret_cast<const uint32_t *>(wsb + lay.pa_list);
         sw.ovf = reinterpret_cast<uint32_t *>(wsb + lay.ovf);
@@ -559,7 +613,8 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         const uint64_t nb = ((uint64_t)Q * (lay.ntiles + 1) + BLOCK - 1) / BLOCK;
         if (nb > 0x7fffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
         ADACOMP_LAUNCH(ADACOMP_KERNEL_BOUNDS, k_bounds, dim3((unsigned)nb), dim3(BLOCK), s, sw,
-                       reinterpret_cast<uint32_t *>(wsb + lay.bounds));
+                       reinterpret_cast<uint32_t *>(wsb + lay.bounds),
+                       reinterpret_cast<uint32_t *>(wsb + lay.tile_tensor));
         CHECK_LAUNCH();
         ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep, dim3((unsigned)lay.ntiles), dim3(BLOCK), s, sw);
         CHECK_LAUNCH();
