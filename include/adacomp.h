@@ -175,7 +175,9 @@ enum {
     ADACOMP_KERNEL_SAMPLE_HIST,    /* select: histogram of a strided sample                     */
     ADACOMP_KERNEL_PICK,           /* select: choose the filter threshold                       */
     ADACOMP_KERNEL_FILTER,         /* select: streaming read + ordered candidate compaction     */
-    ADACOMP_KERNEL_CHECK,          /* select: candidates sufficient?                            */
+    ADACOMP_KERNEL_CHECK,          /* select: candidates sufficient?  offsets of their regions  */
+    ADACOMP_KERNEL_GATHER,         /* select: pack the candidate regions per tensor             */
+    ADACOMP_KERNEL_WORK,           /* select: chunk numbering across tensors                    */
     ADACOMP_KERNEL_HIST,           /* select: radix-descent histogram (3 levels)                */
     ADACOMP_KERNEL_RESOLVE,        /* select: radix-descent bin choice (3 levels)               */
     ADACOMP_KERNEL_COUNT_SEG,      /* select: per-segment counts above / at the threshold       */

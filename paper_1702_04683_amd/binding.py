@@ -206,7 +206,7 @@ def adacomp_apply(params, state, updates, lr, workspace, stream=None):
     return state
 
 
-KERNEL_COUNT = 17
+KERNEL_COUNT = 19
 
 
 def adacomp_kernel_name(kernel_id):

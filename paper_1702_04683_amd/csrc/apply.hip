@@ -173,29 +173,6 @@ __global__ __launch_bounds__(BLOCK) void k_bounds(Sweep sw, uint32_t *B, uint32_
     B[g] = (uint32_t)lo;
 }
 
-// Exclusive prefix sum over the workgroup; `total` receives the sum.  s_wave: WAVES words.
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *s_wave, uint32_t &total) {
-    const uint32_t lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
-    uint32_t incl = x;
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        const uint32_t y = __shfl_up(incl, d);
-        if (lane >= (uint32_t)d) incl += y;
-    }
-    if (lane == WAVE - 1) s_wave[wave] = incl;
-    __syncthreads();
-    uint32_t base = 0;
-    total = 0;
-#pragma unroll
-    for (uint32_t w = 0; w < WAVES; ++w) {
-        const uint32_t s = s_wave[w];
-        if (w < wave) base += s;
-        total += s;
-    }
-    __syncthreads();
-    return base + incl - x;
-}
-
 // Slices of up to PASS consecutive updates (q0 ..) inside tile t, laid end to end.
 struct Slices {
     uint32_t off[PASS + 1];      // position of the first entry of update q0+i; off[n] = entries
@@ -220,7 +197,7 @@ __device__ __forceinline__ uint32_t load_slices(const Sweep &sw, uint32_t t, uin
         sl.tag[threadIdx.x] = q | ((q - u.pull) << 15);
     }
     uint32_t total;
-    const uint32_t o = block_exclusive_scan(len, s_wave, total);
+    const uint32_t o = block_exclusive_scan<WAVES>(len, s_wave, total);
     if (threadIdx.x <= PASS) sl.off[threadIdx.x] = o;  // off[n_slices .. PASS] = total
     if (mine) sl.b0[threadIdx.x] = b0;
     __syncthreads();
@@ -308,7 +285,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
         uint32_t sum = 0;
         for (uint32_t j = 0; j < per_thread; ++j) sum += s_cur[slot(tid * per_thread + j)];
         uint32_t all;
-        uint32_t run = block_exclusive_scan(sum, s_wave, all);
+        uint32_t run = block_exclusive_scan<WAVES>(sum, s_wave, all);
         for (uint32_t j = 0; j < per_thread; ++j) {
             const uint32_t n_touch = s_cur[slot(tid * per_thread + j)];
             s_cur[slot(tid * per_thread + j)] = run;

@@ -26,6 +26,31 @@ __device__ __forceinline__ uint32_t popc64(uint64_t m) { return (uint32_t)__popc
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Exclusive prefix sum of x over a workgroup of NWAVES full waves; `total` receives the
+// sum.  s_wave: NWAVES words of LDS, free for reuse when the call returns.
+template <uint32_t NWAVES>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *s_wave, uint32_t &total) {
+    const uint32_t lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    uint32_t incl = x;
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        const uint32_t y = __shfl_up(incl, d);
+        if (lane >= (uint32_t)d) incl += y;
+    }
+    if (lane == WAVE - 1) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0;
+    total = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < NWAVES; ++w) {
+        const uint32_t s = s_wave[w];
+        if (w < wave) base += s;
+        total += s;
+    }
+    __syncthreads();
+    return base + incl - x;
+}
+
 // Asynchronous host->device upload of small tables through kernel arguments.
 // The payload travels inside the launch packet, so the host buffer may be freed
 // as soon as the call returns, no pinned memory is needed and the copy can be

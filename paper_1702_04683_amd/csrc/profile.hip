@@ -85,6 +85,8 @@ extern "C" const char *adacomp_kernel_name(int id) {
         case ADACOMP_KERNEL_PICK: return "pick";
         case ADACOMP_KERNEL_FILTER: return "filter";
         case ADACOMP_KERNEL_CHECK: return "check";
+        case ADACOMP_KERNEL_GATHER: return "gather";
+        case ADACOMP_KERNEL_WORK: return "work";
         case ADACOMP_KERNEL_HIST: return "hist";
         case ADACOMP_KERNEL_RESOLVE: return "resolve";
         case ADACOMP_KERNEL_COUNT_SEG: return "count";

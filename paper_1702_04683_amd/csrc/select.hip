@@ -13,15 +13,19 @@
 //   3. filter             the one full streaming read: every wave owns a contiguous
 //                         8192-element segment and compacts, in index order, the
 //                         entries with key >= t_lo into its own candidate region;
-//   4. check              a tensor whose candidates are fewer than k or overflowed a
-//                         region is switched to the dense source (always exact);
-//   5. radix descent      12 + 12 + 7 bit histograms over the candidates (or the dense
-//                         tensor) give the exact threshold key T and the tie quota r;
-//   6. count / scan / emit  per-segment counts of key > T and key == T, their
-//                         exclusive scans, and the order-preserving write of exactly k
+//   4. check              per tensor: scan of the region fill counts; a tensor whose
+//                         candidates are fewer than k, overflowed a region or exceed a
+//                         quarter of the tensor is switched to the dense source (the
+//                         tensor itself), so exactness never depends on the sample;
+//   5. gather             the regions are packed, in index order, into one dense
+//                         (index, value) array per tensor;
+//   6. radix descent      12 + 12 + 7 bit histograms over the packed candidates (or the
+//                         dense source) give the exact threshold key T and tie quota r;
+//   7. count / scan / emit  per-chunk counts of key > T and key == T, their exclusive
+//                         scans, and the order-preserving write of exactly k
 //                         (index, value) pairs.
 // Tensors with k == n are copied (identity), tensors with k == 0 produce nothing,
-// tensors with k > n/8 skip steps 1-4.
+// tensors with k > n/8 skip steps 1-5.
 #include <algorithm>
 #include <cstring>
 #include <cmath>
@@ -33,10 +37,12 @@ namespace adacomp {
 namespace {
 
 constexpr uint32_t WSEG = 8192;     // elements per wave segment
-constexpr uint32_t ROUND = 1024;    // elements per wave iteration: 4 x (64 lanes x float4)
+constexpr int FILTER_NLOAD = 2;     // 16-byte loads per lane in flight in the filter (measured best: 2, then 1, then 4)
 constexpr uint32_t PIECE = 256;     // elements per wave-wide float4 load
 constexpr uint32_t BINS = 4096;     // histogram bins (12 key bits)
-constexpr uint32_t HSEGS = 64;      // segments per histogram workgroup
+constexpr uint32_t VCHUNK = 2048;   // packed candidates per wave chunk (descent, count, emit)
+constexpr uint32_t GSEGS = 16;      // segments per wave in the gather
+constexpr uint32_t TAIL_BLOCKS = 1024;  // workgroups of the descent / count / emit kernels
 constexpr uint32_t SPIECES = 64;    // sampled pieces per sample-histogram workgroup
 constexpr uint32_t BLOCK = 256;     // threads per workgroup = 4 waves
 constexpr uint32_t WAVES = BLOCK / WAVE;
@@ -60,8 +66,8 @@ struct LayerDesc {
     uint32_t target;     // sample count the filter threshold must cover
     uint32_t sblk_base;  // prefix sums of workgroup counts, one per kernel shape
     uint32_t wblk_base;  //   one segment per wave
-    uint32_t hblk_base;  //   HSEGS segments per workgroup
     uint32_t iblk_base;  //   identity copy
+    uint32_t gblk_base;  //   GSEGS segments per wave (gather)
     uint32_t pad;
 };
 static_assert(sizeof(LayerDesc) % 8 == 0, "descriptor table is uploaded as 64-bit words");
@@ -73,7 +79,8 @@ struct LayerState {
     uint32_t k_rem;      // rank still to resolve inside the prefix
     uint32_t T;          // threshold key
     uint32_t r;          // number of entries with key == T to keep (lowest indices)
-    uint32_t pad[2];
+    uint32_t m;          // elements of the source the descent reads: n, or the number of candidates
+    uint32_t nchunk;     // chunks of that source (WSEG elements of the tensor, VCHUNK candidates)
 };
 
 struct Workspace {
@@ -83,8 +90,11 @@ struct Workspace {
     uint32_t *seg_cnt;    // [nseg_total] candidates found per segment
     uint32_t *seg_gt;     // [nseg_total] #key > T, then exclusive prefix within the tensor
     uint32_t *seg_eq;     // [nseg_total] #key == T, then exclusive prefix within the tensor
-    uint32_t *cand_idx;   // [cand_total]
-    uint32_t *cand_val;   // [cand_total] raw value bits
+    uint32_t *chunk_base; // [L+1] first chunk of every tensor in the global chunk numbering
+    uint32_t *seg_off;    // [nseg_total] candidates of the tensor before this segment
+    uint2 *cand;          // [cand_total] per-segment regions of (index, value bits)
+    uint32_t *pack_idx;   // [cand_total] the same candidates packed per tensor
+    uint32_t *pack_val;
     size_t bytes;
 };
 
@@ -103,7 +113,7 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
               const uint64_t *k_override, Plan &plan) {
     if (!(rate >= 0.0 && rate <= 1.0)) return ADACOMP_ERR_RATE;
     plan.desc.assign((size_t)L + 1, LayerDesc{});
-    uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, hblk = 0, iblk = 0;
+    uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, iblk = 0, gblk = 0;
     for (uint32_t l = 0; l < L; ++l) {
         if (n[l] > 0xffffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
         uint64_t k64 = k_override ? k_override[l] : adacomp_count(n[l], rate);
@@ -118,8 +128,8 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
         d.seg_base = (uint32_t)seg;
         d.sblk_base = (uint32_t)sblk;
         d.wblk_base = (uint32_t)wblk;
-        d.hblk_base = (uint32_t)hblk;
         d.iblk_base = (uint32_t)iblk;
+        d.gblk_base = (uint32_t)gblk;
         d.npieces = (uint32_t)((n[l] + PIECE - 1) / PIECE);
         d.stride = 1;
         if (d.n == 0 || d.k == 0) {
@@ -157,19 +167,21 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
                     }
                 }
                 double per_seg = m_est * (double)WSEG / (double)n[l];
-                uint64_t cap = (uint64_t)std::ceil(3.0 * per_seg) + 64;
+                // a multiple of 16 entries: every region starts on a 128-byte line and is
+                // written in whole lines
+                uint64_t cap = ((uint64_t)std::ceil(3.0 * per_seg) + 64 + 15) & ~15ull;
                 d.cap = (uint32_t)std::min<uint64_t>(cap, WSEG);
                 cand += (uint64_t)d.nseg * d.cap;
                 sblk += (d.npieces_s + SPIECES - 1) / SPIECES;
+                gblk += (d.nseg + WAVES * GSEGS - 1) / (WAVES * GSEGS);
             }
             seg += d.nseg;
             wblk += (d.nseg + WAVES - 1) / WAVES;
-            hblk += (d.nseg + HSEGS - 1) / HSEGS;
         }
         out += d.k;
     }
     if (seg > 0xffffffffull || sblk > 0x7fffffffull || wblk > 0x7fffffffull ||
-        hblk > 0x7fffffffull || iblk > 0x7fffffffull)
+        iblk > 0x7fffffffull || gblk > 0x7fffffffull)
         return ADACOMP_ERR_LAYER_TOO_LARGE;
     LayerDesc &e = plan.desc[L];
     e.out_off = out;
@@ -177,8 +189,8 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
     e.seg_base = (uint32_t)seg;
     e.sblk_base = (uint32_t)sblk;
     e.wblk_base = (uint32_t)wblk;
-    e.hblk_base = (uint32_t)hblk;
     e.iblk_base = (uint32_t)iblk;
+    e.gblk_base = (uint32_t)gblk;
     plan.nseg_total = seg;
     plan.cand_total = cand;
     plan.out_total = out;
@@ -198,8 +210,11 @@ void carve(const Plan &plan, uint32_t L, void *base, Workspace &ws) {
     ws.seg_cnt = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
     ws.seg_gt = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
     ws.seg_eq = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
-    ws.cand_idx = (uint32_t *)take(plan.cand_total * sizeof(uint32_t));
-    ws.cand_val = (uint32_t *)take(plan.cand_total * sizeof(uint32_t));
+    ws.chunk_base = (uint32_t *)take(((size_t)L + 1) * sizeof(uint32_t));
+    ws.seg_off = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
+    ws.cand = (uint2 *)take(plan.cand_total * sizeof(uint2));
+    ws.pack_idx = (uint32_t *)take(plan.cand_total * sizeof(uint32_t));
+    ws.pack_val = (uint32_t *)take(plan.cand_total * sizeof(uint32_t));
     ws.bytes = off;
 }
 
@@ -215,12 +230,29 @@ __device__ __forceinline__ uint32_t find_layer(const LayerDesc *d, uint32_t L, u
     return lo;
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// Tensor pointers come out of descriptor tables in memory, so the compiler cannot tell that
+// they point to device global memory and would emit generic (flat) loads; these typedefs say so.
+typedef const __attribute__((address_space(1))) uint32_t *global_u32_ptr;
+typedef const __attribute__((address_space(1))) u32x4 *global_u32x4_ptr;
+
+// 16 bytes at element `base` of a 16-byte aligned array.  STREAM marks data that is read
+// once (non-temporal: it does not displace cached lines).
+template <bool STREAM>
+__device__ __forceinline__ uint4 load4_full(const float *g, uint32_t base) {
+    global_u32x4_ptr p = (global_u32x4_ptr)(reinterpret_cast<const uint32_t *>(g) + base);
+    const u32x4 t = STREAM ? __builtin_nontemporal_load(p) : *p;
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 // Four consecutive elements starting at `base`; elements at or beyond `lim` read as 0.
+template <bool STREAM = false>
 __device__ __forceinline__ uint4 load4(const float *g, uint32_t base, uint32_t lim, bool vec) {
     uint4 v = make_uint4(0, 0, 0, 0);
     if (base >= lim) return v;
-    const uint32_t *p = reinterpret_cast<const uint32_t *>(g) + base;
-    if (vec && lim - base >= 4) return *reinterpret_cast<const uint4 *>(p);
+    if (vec && lim - base >= 4) return load4_full<STREAM>(g, base);
+    global_u32_ptr p = (global_u32_ptr)(reinterpret_cast<const uint32_t *>(g) + base);
     v.x = p[0];
     if (lim - base > 1) v.y = p[1];
     if (lim - base > 2) v.z = p[2];
@@ -228,54 +260,73 @@ __device__ __forceinline__ uint4 load4(const float *g, uint32_t base, uint32_t l
     return v;
 }
 
-// Visit the elements [lo, hi) of a tensor with one wave, in index order: the visitor
-// is called wave-wide once per 256-element piece with each lane holding 4 consecutive
-// elements (idx[c] = first + c, bits[c]); nvalid of them are inside the range.
-template <class F>
-__device__ __forceinline__ void visit_dense(const float *g, bool vec, uint32_t lo, uint32_t hi, F &&f) {
+// What the descent, count and emit kernels read for one tensor: the tensor itself (position
+// is the index) or its packed candidates (explicit index array).
+struct Source {
+    const uint32_t *val;  // value bits
+    const uint32_t *idx;  // explicit indices, or nullptr when the position is the index
+    uint32_t m;           // elements
+    uint32_t chunk;       // elements per wave chunk
+    bool vec;             // 16-byte aligned
+};
+
+// Visit the elements [lo, hi) of a source with one wave, in order: the visitor is called
+// wave-wide once per 256-element piece with each lane holding 4 consecutive elements
+// (idx[c], bits[c]); nvalid of them are inside the range.  WITH_IDX loads explicit indices.
+template <bool WITH_IDX, bool STREAM = false, int NLOAD = 4, class F>
+__device__ __forceinline__ void visit_range(const Source &src, uint32_t lo, uint32_t hi, F &&f) {
     const uint32_t lane = threadIdx.x & (WAVE - 1);
-    for (uint32_t r = lo; r < hi; r += ROUND) {
-        uint4 v[4];
+    const float *vals = reinterpret_cast<const float *>(src.val);
+    const float *idxs = reinterpret_cast<const float *>(src.idx);
+    const bool with_idx = WITH_IDX && idxs != nullptr;
+    constexpr uint32_t round = NLOAD * PIECE;  // elements per wave iteration: NLOAD 16-byte loads per lane in flight
+    uint32_t r = lo;
+    if (src.vec) {
+        // whole rounds of an aligned source: plain vector loads, every element valid
+        for (; hi - r >= round; r += round) {
+            uint4 v[NLOAD], x[NLOAD];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = load4(g, r + j * PIECE + lane * 4, hi, vec);
+            for (int j = 0; j < NLOAD; ++j) v[j] = load4_full<STREAM>(vals, r + j * PIECE + lane * 4);
+            if (with_idx) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t first = r + j * PIECE + lane * 4;
-            if (r + j * PIECE >= hi) break;  // wave-uniform
-            const uint32_t idx[4] = {first, first + 1, first + 2, first + 3};
-            const uint32_t bits[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
-            const uint32_t nvalid = first >= hi ? 0u : (hi - first < 4u ? hi - first : 4u);
-            f(idx, bits, nvalid);
+                for (int j = 0; j < NLOAD; ++j) x[j] = load4_full<false>(idxs, r + j * PIECE + lane * 4);
+            }
+#pragma unroll
+            for (int j = 0; j < NLOAD; ++j) {
+                const uint32_t first = r + j * PIECE + lane * 4;
+                uint32_t idx[4] = {first, first + 1, first + 2, first + 3};
+                if (with_idx) {
+                    idx[0] = x[j].x;
+                    idx[1] = x[j].y;
+                    idx[2] = x[j].z;
+                    idx[3] = x[j].w;
+                }
+                const uint32_t bits[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+                f(idx, bits, 4u);
+            }
         }
     }
-}
-
-// Visit the candidates of one segment with one wave, in index order, one per lane.
-template <class F>
-__device__ __forceinline__ void visit_cand(const uint32_t *cidx, const uint32_t *cval, uint32_t count, F &&f) {
-    const uint32_t lane = threadIdx.x & (WAVE - 1);
-    for (uint32_t e0 = 0; e0 < count; e0 += WAVE) {
-        const uint32_t e = e0 + lane;
-        const uint32_t ok = e < count;
-        const uint32_t idx[1] = {ok ? cidx[e] : 0u};
-        const uint32_t bits[1] = {ok ? cval[e] : 0u};
-        f(idx, bits, ok);
+    // the rest: an unaligned source, or the ragged end of the range
+    for (; r < hi; r += PIECE) {
+        const uint32_t first = r + lane * 4;
+        const uint4 v = load4<STREAM>(vals, first, hi, src.vec);
+        uint32_t idx[4] = {first, first + 1, first + 2, first + 3};
+        if (with_idx) {
+            const uint4 x = load4(idxs, first, hi, src.vec);
+            idx[0] = x.x;
+            idx[1] = x.y;
+            idx[2] = x.z;
+            idx[3] = x.w;
+        }
+        const uint32_t bits[4] = {v.x, v.y, v.z, v.w};
+        const uint32_t nvalid = first >= hi ? 0u : (hi - first < 4u ? hi - first : 4u);
+        f(idx, bits, nvalid);
     }
 }
 
-// Visit segment `seg` of tensor d from whichever source the tensor currently uses.
-template <class F>
-__device__ __forceinline__ void visit_segment(const LayerDesc &d, const LayerState &st, const Workspace &ws,
-                                              uint32_t seg, F &&f) {
-    if (st.use_dense) {
-        const uint32_t lo = seg * WSEG;
-        const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
-        visit_dense(d.g, d.vec != 0, lo, hi, f);
-    } else {
-        const uint64_t base = d.cand_base + (uint64_t)seg * d.cap;
-        const uint32_t c = ws.seg_cnt[d.seg_base + seg];
-        visit_cand(ws.cand_idx + base, ws.cand_val + base, c < d.cap ? c : d.cap, f);
-    }
+__device__ __forceinline__ Source source_of(const LayerDesc &d, const LayerState &st, const Workspace &ws) {
+    if (st.use_dense) return Source{reinterpret_cast<const uint32_t *>(d.g), nullptr, d.n, WSEG, d.vec != 0};
+    return Source{ws.pack_val + d.cand_base, ws.pack_idx + d.cand_base, st.m, VCHUNK, true};
 }
 
 // Workgroup-wide: the largest bin b of h[0..nbins) whose suffix sum (bins >= b) reaches
@@ -420,13 +471,25 @@ __global__ __launch_bounds__(BLOCK) void k_pick(Workspace ws) {
         st.k_rem = d.k;
         st.T = 0;
         st.r = 0;
-        st.pad[0] = st.pad[1] = 0;
+        st.m = d.n;          // the dense source, unless k_check finds the candidates usable
+        st.nchunk = d.nseg;
         ws.state[l] = st;
     }
 }
 
 // ---- step 3: the streaming read; ordered compaction of key >= t_lo per wave ------
+// Candidates are staged in LDS (one private buffer per wave) and leave as coalesced
+// 8-byte (index, value) stores: one or two store instructions per segment instead of a
+// scattered 4-byte store per candidate.
+constexpr uint32_t FSTAGE = 272;  // staged candidates per wave: a 256-element piece on top of a 15-entry remainder
+
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L) {
+    __shared__ uint2 s_stage[WAVES][FSTAGE];
     const uint32_t l = find_layer<&LayerDesc::wblk_base>(ws.desc, L, blockIdx.x);
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER) return;
@@ -434,14 +497,39 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L) {
     const uint32_t seg = (blockIdx.x - d.wblk_base) * WAVES + wave;
     if (seg >= d.nseg) return;
     const uint32_t t_lo = ws.state[l].t_lo;
-    const uint64_t base = d.cand_base + (uint64_t)seg * d.cap;
-    uint32_t *cidx = ws.cand_idx + base;
-    uint32_t *cval = ws.cand_val + base;
+    uint2 *region = ws.cand + d.cand_base + (uint64_t)seg * d.cap;
+    uint2 *stage = s_stage[wave];
     const uint32_t cap = d.cap;
     const uint32_t lo = seg * WSEG;
     const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
-    uint32_t run = 0;  // candidates found so far in this segment (wave-uniform)
-    visit_dense(d.g, d.vec != 0, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+    const Source src{reinterpret_cast<const uint32_t *>(d.g), nullptr, d.n, WSEG, d.vec != 0};
+    uint32_t staged = 0;   // candidates in the stage (wave-uniform)
+    uint32_t written = 0;  // candidates of this segment already flushed (may exceed cap: those are dropped)
+    // Whole 128-byte lines (16 entries) only: `written` stays a multiple of 16 until the last
+    // flush, which rounds up (the slack holds stale LDS contents and is never read, the
+    // region's fill count says where it ends).  Entries past cap are counted, not stored.
+    auto flush = [&](bool last) {
+        wave_lds_fence();
+        const uint32_t n_out = last ? (staged + 15u) & ~15u : staged & ~15u;
+        for (uint32_t e = lane; e < n_out; e += WAVE) {
+            if (written + e < cap) {  // streaming store: the line is not needed in cache again soon
+                const uint2 c = stage[e];
+                u32x2 t;
+                t.x = c.x;
+                t.y = c.y;
+                __builtin_nontemporal_store(t, reinterpret_cast<u32x2 *>(&region[written + e]));
+            }
+        }
+        const uint32_t keep = last ? 0u : staged - n_out;  // < 16 entries move to the front
+        uint2 moved = make_uint2(0, 0);
+        if (lane < keep) moved = stage[n_out + lane];
+        wave_lds_fence();
+        if (lane < keep) stage[lane] = moved;
+        wave_lds_fence();
+        written += last ? staged : n_out;
+        staged = keep;
+    };
+    visit_range<false, true, FILTER_NLOAD>(src, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
         bool f[4];
         uint64_t m[4];
 #pragma unroll
@@ -450,87 +538,174 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L) {
             m[c] = __ballot(f[c]);
         }
         if ((m[0] | m[1] | m[2] | m[3]) == 0) return;
-        uint32_t pos = run + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
+        const uint32_t found = popc64(m[0]) + popc64(m[1]) + popc64(m[2]) + popc64(m[3]);
+        if (staged + found > FSTAGE) flush(false);
+        uint32_t pos = staged + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (f[c]) {
-                if (pos < cap) {
-                    cidx[pos] = idx[c];
-                    cval[pos] = bits[c];
-                }
-                ++pos;
-            }
+            if (f[c]) stage[pos++] = make_uint2(idx[c], bits[c]);
         }
-        run += popc64(m[0]) + popc64(m[1]) + popc64(m[2]) + popc64(m[3]);
+        staged += found;
     });
-    if (lane == 0) ws.seg_cnt[d.seg_base + seg] = run;
+    flush(true);
+    if (lane == 0) ws.seg_cnt[d.seg_base + seg] = written;
 }
 
-// ---- step 4: enough candidates, and none lost? -----------------------------------
+// ---- step 4: candidate offsets per segment; are the candidates usable? -------------
 __global__ __launch_bounds__(BLOCK) void k_check(Workspace ws) {
-    __shared__ unsigned long long s_total;
+    __shared__ uint32_t s_wave[WAVES];
     __shared__ uint32_t s_over;
     const uint32_t l = blockIdx.x;
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER) return;
-    if (threadIdx.x == 0) {
-        s_total = 0;
-        s_over = 0;
-    }
+    if (threadIdx.x == 0) s_over = 0;
     __syncthreads();
-    unsigned long long total = 0;
-    uint32_t over = 0;
-    for (uint32_t s = threadIdx.x; s < d.nseg; s += BLOCK) {
-        const uint32_t c = ws.seg_cnt[d.seg_base + s];
-        total += c;
+    uint32_t carry = 0;
+    bool over = false;
+    for (uint32_t s0 = 0; s0 < d.nseg; s0 += BLOCK) {
+        const uint32_t s = s0 + threadIdx.x;
+        uint32_t c = s < d.nseg ? ws.seg_cnt[d.seg_base + s] : 0u;
         over |= c > d.cap;
+        c = c < d.cap ? c : d.cap;
+        uint32_t total;
+        const uint32_t o = block_exclusive_scan<WAVES>(c, s_wave, total);
+        if (s < d.nseg) ws.seg_off[d.seg_base + s] = carry + o;
+        carry += total;  // cannot wrap: at most n candidates
     }
-    atomicAdd(&s_total, total);
-    if (over) atomicOr(&s_over, 1u);
+    if (over) s_over = 1;
     __syncthreads();
-    if (threadIdx.x == 0 && (s_over || s_total < d.k)) ws.state[l].use_dense = 1;
+    if (threadIdx.x == 0) {
+        const uint32_t m = carry;
+        if (s_over || m < d.k || m > d.n / 4) {
+            ws.state[l].use_dense = 1;  // m and nchunk keep the dense-source values
+        } else {
+            ws.state[l].m = m;
+            ws.state[l].nchunk = (m + VCHUNK - 1) / VCHUNK;
+        }
+    }
 }
 
-// ---- step 5: radix descent, one histogram + one resolve per level ----------------
+// ---- step 5: pack the candidate regions of a tensor, in index order ------------------
+__global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L) {
+    const uint32_t l = find_layer<&LayerDesc::gblk_base>(ws.desc, L, blockIdx.x);
+    const LayerDesc d = ws.desc[l];
+    if (d.mode != MODE_FILTER || ws.state[l].use_dense) return;
+    const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+    const uint32_t s0 = ((blockIdx.x - d.gblk_base) * WAVES + wave) * GSEGS;
+    if (s0 >= d.nseg) return;
+    uint32_t my_cnt = 0, my_off = 0;
+    if (lane < GSEGS && s0 + lane < d.nseg) {
+        my_cnt = ws.seg_cnt[d.seg_base + s0 + lane];
+        my_off = ws.seg_off[d.seg_base + s0 + lane];
+    }
+    const uint2 *__restrict__ cand = ws.cand + d.cand_base + (uint64_t)s0 * d.cap;
+    uint32_t *__restrict__ pidx = ws.pack_idx + d.cand_base;
+    uint32_t *__restrict__ pval = ws.pack_val + d.cand_base;
+    uint32_t cnt[GSEGS], off[GSEGS];
+    uint2 rc[GSEGS];
+#pragma unroll
+    for (uint32_t i = 0; i < GSEGS; ++i) {  // first 64 candidates of every segment, loads together
+        cnt[i] = __shfl(my_cnt, i);
+        cnt[i] = cnt[i] < d.cap ? cnt[i] : d.cap;
+        off[i] = __shfl(my_off, i);
+        if (lane < cnt[i]) rc[i] = cand[(uint64_t)i * d.cap + lane];
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < GSEGS; ++i) {
+        if (lane < cnt[i]) {
+            pidx[off[i] + lane] = rc[i].x;
+            pval[off[i] + lane] = rc[i].y;
+        }
+        for (uint32_t e = WAVE + lane; e < cnt[i]; e += WAVE) {  // fuller segments
+            const uint2 c = cand[(uint64_t)i * d.cap + e];
+            pidx[off[i] + e] = c.x;
+            pval[off[i] + e] = c.y;
+        }
+    }
+}
+
+// ---- chunk numbering across tensors ------------------------------------------------
+// The descent, count and emit kernels run with a fixed number of workgroups; each worker
+// (workgroup or wave) takes a contiguous range of the global chunk numbering.
+__global__ __launch_bounds__(BLOCK) void k_work(Workspace ws, uint32_t L) {
+    __shared__ uint32_t s_wave[WAVES];
+    uint32_t carry = 0;
+    for (uint32_t l0 = 0; l0 < L; l0 += BLOCK) {
+        const uint32_t l = l0 + threadIdx.x;
+        const uint32_t c = l < L ? ws.state[l].nchunk : 0u;
+        uint32_t total;
+        const uint32_t o = block_exclusive_scan<WAVES>(c, s_wave, total);
+        if (l < L) ws.chunk_base[l] = carry + o;
+        carry += total;
+    }
+    if (threadIdx.x == 0) ws.chunk_base[L] = carry;
+}
+
+// Range of global chunk numbers of worker `w` out of `nworkers`, and the tensor of its first chunk.
+__device__ __forceinline__ bool chunk_range(const Workspace &ws, uint32_t L, uint32_t w, uint32_t nworkers,
+                                            uint32_t &lo, uint32_t &hi, uint32_t &l) {
+    const uint32_t total = ws.chunk_base[L];
+    const uint32_t per = (total + nworkers - 1) / nworkers;
+    lo = w * per;
+    if (per == 0 || lo >= total) return false;
+    hi = total - lo < per ? total : lo + per;
+    uint32_t a = 0, b = L;  // the last tensor with chunk_base <= lo
+    while (b - a > 1) {
+        const uint32_t mid = (a + b) >> 1;
+        if (ws.chunk_base[mid] <= lo) a = mid; else b = mid;
+    }
+    l = a;
+    return true;
+}
+
+// ---- step 6: radix descent, one histogram + one resolve per level ----------------
 // level 0: bins = key[30:19]; level 1: key[30:19] == prefix, bins = key[18:7];
 // level 2: key[30:7] == prefix, bins = key[6:0].
 template <int LEVEL>
 __global__ __launch_bounds__(BLOCK) void k_hist(Workspace ws, uint32_t L) {
     __shared__ uint32_t h[BINS];
-    const uint32_t l = find_layer<&LayerDesc::hblk_base>(ws.desc, L, blockIdx.x);
-    const LayerDesc d = ws.desc[l];
-    const LayerState st = ws.state[l];
+    uint32_t w_lo, w_hi, l;
+    if (!chunk_range(ws, L, blockIdx.x, gridDim.x, w_lo, w_hi, l)) return;
     const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
-    const uint32_t s_lo = (blockIdx.x - d.hblk_base) * HSEGS;
-    const uint32_t s_hi = s_lo + HSEGS < d.nseg ? s_lo + HSEGS : d.nseg;
-    lds_hist_clear(h);
-    uint32_t zero_run = 0;
-    const uint32_t prefix = st.prefix;
-    for (uint32_t seg = s_lo + wave; seg < s_hi; seg += WAVES) {
-        visit_segment(d, st, ws, seg, [&](const auto &idx, const auto &bits, uint32_t nvalid) {
-            constexpr int NC = sizeof(bits) / sizeof(bits[0]);
-            uint32_t key[NC], bin[NC];
-            bool match[NC];
+    while (w_lo < w_hi) {  // one tensor at a time: the LDS histogram belongs to one tensor
+        while (w_lo >= ws.chunk_base[l + 1]) ++l;
+        const uint32_t base = ws.chunk_base[l];
+        const uint32_t end = ws.chunk_base[l + 1] < w_hi ? ws.chunk_base[l + 1] : w_hi;
+        const LayerDesc d = ws.desc[l];
+        const LayerState st = ws.state[l];
+        const Source src = source_of(d, st, ws);
+        const uint32_t prefix = st.prefix;
+        lds_hist_clear(h);
+        uint32_t zero_run = 0;
+        for (uint32_t w = w_lo + wave; w < end; w += WAVES) {
+            const uint32_t lo = (w - base) * src.chunk;
+            const uint32_t hi = src.m - lo < src.chunk ? src.m : lo + src.chunk;
+            visit_range<false>(src, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+                uint32_t key[4], bin[4];
+                bool match[4];
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                key[c] = mag_key(bits[c]);
-                match[c] = (uint32_t)c < nvalid;
-                if (LEVEL == 0) {
-                    bin[c] = key[c] >> 19;
-                } else if (LEVEL == 1) {
-                    match[c] = match[c] && (key[c] >> 19) == prefix;
-                    bin[c] = (key[c] >> 7) & 0xfffu;
-                } else {
-                    match[c] = match[c] && (key[c] >> 7) == prefix;
-                    bin[c] = key[c] & 0x7fu;
+                for (int c = 0; c < 4; ++c) {
+                    key[c] = mag_key(bits[c]);
+                    match[c] = (uint32_t)c < nvalid;
+                    if (LEVEL == 0) {
+                        bin[c] = key[c] >> 19;
+                    } else if (LEVEL == 1) {
+                        match[c] = match[c] && (key[c] >> 19) == prefix;
+                        bin[c] = (key[c] >> 7) & 0xfffu;
+                    } else {
+                        match[c] = match[c] && (key[c] >> 7) == prefix;
+                        bin[c] = key[c] & 0x7fu;
+                    }
                 }
-            }
-            (void)idx;
-            lds_hist_add<NC>(h, key, match, bin, zero_run);
-        });
+                (void)idx;
+                lds_hist_add<4>(h, key, match, bin, zero_run);
+            });
+        }
+        if (lane == 0 && zero_run) atomicAdd(&h[0], zero_run);
+        lds_hist_flush(h, ws.hist + (size_t)l * BINS, LEVEL == 2 ? 128u : BINS);
+        __syncthreads();
+        w_lo = end;
     }
-    if (lane == 0 && zero_run) atomicAdd(&h[0], zero_run);
-    lds_hist_flush(h, ws.hist + (size_t)l * BINS, LEVEL == 2 ? 128u : BINS);
 }
 
 template <int LEVEL>
@@ -556,117 +731,133 @@ __global__ __launch_bounds__(BLOCK) void k_resolve(Workspace ws) {
     }
 }
 
-// ---- step 6: per-segment counts, scans, ordered emit ------------------------------
+// ---- step 7: per-chunk counts, scans, ordered emit ------------------------------
 __global__ __launch_bounds__(BLOCK) void k_count(Workspace ws, uint32_t L) {
-    const uint32_t l = find_layer<&LayerDesc::wblk_base>(ws.desc, L, blockIdx.x);
-    const LayerDesc d = ws.desc[l];
     const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
-    const uint32_t seg = (blockIdx.x - d.wblk_base) * WAVES + wave;
-    if (seg >= d.nseg) return;
-    const LayerState st = ws.state[l];
-    const uint32_t T = st.T;
-    uint32_t gt = 0, eq = 0;
-    visit_segment(d, st, ws, seg, [&](const auto &idx, const auto &bits, uint32_t nvalid) {
-        constexpr int NC = sizeof(bits) / sizeof(bits[0]);
-        (void)idx;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const uint32_t key = mag_key(bits[c]);
-            const bool ok = (uint32_t)c < nvalid;
-            gt += popc64(__ballot(ok && key > T));
-            eq += popc64(__ballot(ok && key == T));
+    uint32_t w_lo, w_hi, l;
+    if (!chunk_range(ws, L, blockIdx.x * WAVES + wave, gridDim.x * WAVES, w_lo, w_hi, l)) return;
+    uint32_t cur = 0xffffffffu;
+    LayerDesc d;
+    LayerState st;
+    Source src;
+    for (uint32_t w = w_lo; w < w_hi; ++w) {
+        while (w >= ws.chunk_base[l + 1]) ++l;
+        if (l != cur) {
+            cur = l;
+            d = ws.desc[l];
+            st = ws.state[l];
+            src = source_of(d, st, ws);
         }
-    });
-    if (lane == 0) {
-        ws.seg_gt[d.seg_base + seg] = gt;
-        ws.seg_eq[d.seg_base + seg] = eq;
+        const uint32_t j = w - ws.chunk_base[l];
+        const uint32_t lo = j * src.chunk;
+        const uint32_t hi = src.m - lo < src.chunk ? src.m : lo + src.chunk;
+        const uint32_t T = st.T;
+        uint32_t gt = 0, eq = 0;
+        visit_range<false>(src, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+            (void)idx;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t key = mag_key(bits[c]);
+                const bool ok = (uint32_t)c < nvalid;
+                gt += popc64(__ballot(ok && key > T));
+                eq += popc64(__ballot(ok && key == T));
+            }
+        });
+        if (lane == 0) {
+            ws.seg_gt[d.seg_base + j] = gt;
+            ws.seg_eq[d.seg_base + j] = eq;
+        }
     }
 }
 
-// Exclusive scan over the segments of one tensor of both count arrays, in place.
+// Exclusive scan over the chunks of one tensor of both count arrays, in place.
 __global__ __launch_bounds__(BLOCK) void k_scan(Workspace ws) {
-    __shared__ uint32_t s_a[BLOCK], s_b[BLOCK];
+    __shared__ uint32_t s_wave[WAVES];
     const uint32_t l = blockIdx.x;
     const LayerDesc d = ws.desc[l];
     if (d.nseg == 0) return;
+    const uint32_t nchunk = ws.state[l].nchunk;
     uint32_t *gt = ws.seg_gt + d.seg_base, *eq = ws.seg_eq + d.seg_base;
-    const uint32_t t = threadIdx.x;
     uint32_t carry_a = 0, carry_b = 0;
-    for (uint32_t s0 = 0; s0 < d.nseg; s0 += BLOCK) {
-        const uint32_t s = s0 + t;
-        const uint32_t a = s < d.nseg ? gt[s] : 0u, b = s < d.nseg ? eq[s] : 0u;
-        s_a[t] = a;
-        s_b[t] = b;
-        __syncthreads();
-        for (uint32_t step = 1; step < BLOCK; step <<= 1) {  // inclusive prefix scan
-            const uint32_t xa = t >= step ? s_a[t - step] : 0u, xb = t >= step ? s_b[t - step] : 0u;
-            __syncthreads();
-            s_a[t] += xa;
-            s_b[t] += xb;
-            __syncthreads();
+    for (uint32_t s0 = 0; s0 < nchunk; s0 += BLOCK) {
+        const uint32_t s = s0 + threadIdx.x;
+        const uint32_t a = s < nchunk ? gt[s] : 0u, b = s < nchunk ? eq[s] : 0u;
+        uint32_t ta, tb;
+        const uint32_t xa = block_exclusive_scan<WAVES>(a, s_wave, ta);
+        const uint32_t xb = block_exclusive_scan<WAVES>(b, s_wave, tb);
+        if (s < nchunk) {
+            gt[s] = carry_a + xa;
+            eq[s] = carry_b + xb;
         }
-        if (s < d.nseg) {
-            gt[s] = carry_a + s_a[t] - a;
-            eq[s] = carry_b + s_b[t] - b;
-        }
-        carry_a += s_a[BLOCK - 1];
-        carry_b += s_b[BLOCK - 1];
-        __syncthreads();
+        carry_a += ta;
+        carry_b += tb;
     }
 }
 
 __global__ __launch_bounds__(BLOCK) void k_emit(Workspace ws, uint32_t L, uint32_t *out_idx, uint32_t *out_val) {
-    const uint32_t l = find_layer<&LayerDesc::wblk_base>(ws.desc, L, blockIdx.x);
-    const LayerDesc d = ws.desc[l];
     const uint32_t wave = threadIdx.x / WAVE;
-    const uint32_t seg = (blockIdx.x - d.wblk_base) * WAVES + wave;
-    if (seg >= d.nseg) return;
-    const LayerState st = ws.state[l];
-    const uint32_t T = st.T, r = st.r;
-    uint32_t run_gt = ws.seg_gt[d.seg_base + seg];  // entries with key > T before this segment
-    uint32_t run_eq = ws.seg_eq[d.seg_base + seg];  // entries with key == T before this segment
-    uint32_t *oi = out_idx + d.out_off;
-    uint32_t *ov = out_val + d.out_off;
-    visit_segment(d, st, ws, seg, [&](const auto &idx, const auto &bits, uint32_t nvalid) {
-        constexpr int NC = sizeof(bits) / sizeof(bits[0]);
-        bool g[NC], e[NC];
-        uint64_t mg[NC], me[NC];
-        uint64_t any = 0;
-        uint32_t gt_b = run_gt, eq_b = run_eq, tot_g = 0, tot_e = 0;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const uint32_t key = mag_key(bits[c]);
-            const bool ok = (uint32_t)c < nvalid;
-            g[c] = ok && key > T;
-            e[c] = ok && key == T;
-            mg[c] = __ballot(g[c]);
-            me[c] = __ballot(e[c]);
-            any |= mg[c] | me[c];
-            gt_b += lanes_below(mg[c]);
-            eq_b += lanes_below(me[c]);
-            tot_g += popc64(mg[c]);
-            tot_e += popc64(me[c]);
+    uint32_t w_lo, w_hi, l;
+    if (!chunk_range(ws, L, blockIdx.x * WAVES + wave, gridDim.x * WAVES, w_lo, w_hi, l)) return;
+    uint32_t cur = 0xffffffffu;
+    LayerDesc d;
+    LayerState st;
+    Source src;
+    for (uint32_t w = w_lo; w < w_hi; ++w) {
+        while (w >= ws.chunk_base[l + 1]) ++l;
+        if (l != cur) {
+            cur = l;
+            d = ws.desc[l];
+            st = ws.state[l];
+            src = source_of(d, st, ws);
         }
-        if (any == 0) return;
+        const uint32_t j = w - ws.chunk_base[l];
+        const uint32_t lo = j * src.chunk;
+        const uint32_t hi = src.m - lo < src.chunk ? src.m : lo + src.chunk;
+        const uint32_t T = st.T, r = st.r;
+        uint32_t run_gt = ws.seg_gt[d.seg_base + j];  // entries with key > T before this chunk
+        uint32_t run_eq = ws.seg_eq[d.seg_base + j];  // entries with key == T before this chunk
+        uint32_t *oi = out_idx + d.out_off;
+        uint32_t *ov = out_val + d.out_off;
+        visit_range<true>(src, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+            bool g[4], e[4];
+            uint64_t mg[4], me[4];
+            uint64_t any = 0;
+            uint32_t gt_b = run_gt, eq_b = run_eq, tot_g = 0, tot_e = 0;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            if (g[c]) {
-                const uint32_t pos = gt_b + (eq_b < r ? eq_b : r);
-                oi[pos] = idx[c];
-                ov[pos] = bits[c];
-                ++gt_b;
-            } else if (e[c]) {
-                if (eq_b < r) {
-                    const uint32_t pos = gt_b + eq_b;
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t key = mag_key(bits[c]);
+                const bool ok = (uint32_t)c < nvalid;
+                g[c] = ok && key > T;
+                e[c] = ok && key == T;
+                mg[c] = __ballot(g[c]);
+                me[c] = __ballot(e[c]);
+                any |= mg[c] | me[c];
+                gt_b += lanes_below(mg[c]);
+                eq_b += lanes_below(me[c]);
+                tot_g += popc64(mg[c]);
+                tot_e += popc64(me[c]);
+            }
+            if (any == 0) return;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (g[c]) {
+                    const uint32_t pos = gt_b + (eq_b < r ? eq_b : r);
                     oi[pos] = idx[c];
                     ov[pos] = bits[c];
+                    ++gt_b;
+                } else if (e[c]) {
+                    if (eq_b < r) {
+                        const uint32_t pos = gt_b + eq_b;
+                        oi[pos] = idx[c];
+                        ov[pos] = bits[c];
+                    }
+                    ++eq_b;
                 }
-                ++eq_b;
             }
-        }
-        run_gt += tot_g;
-        run_eq += tot_e;
-    });
+            run_gt += tot_g;
+            run_eq += tot_e;
+        });
+    }
 }
 
 // ---- k == n: the update is the tensor itself --------------------------------------
@@ -797,17 +988,21 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
     if (tot.sblk_base) {  // at least one tensor goes through the filter
         LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, tot.wblk_base, ws, L);
         LAUNCH(ADACOMP_KERNEL_CHECK, k_check, L, ws);
+        LAUNCH(ADACOMP_KERNEL_GATHER, k_gather, tot.gblk_base, ws, L);
     }
     if (tot.seg_base) {
-        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<0>, tot.hblk_base, ws, L);
+        // fixed grids: the number of chunks is known on the device only (<= the segments)
+        const uint32_t tail_blocks = (uint32_t)std::min<uint64_t>(TAIL_BLOCKS, (tot.seg_base + WAVES - 1) / WAVES);
+        LAUNCH(ADACOMP_KERNEL_WORK, k_work, 1, ws, L);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<0>, tail_blocks, ws, L);
         LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<0>, L, ws);
-        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<1>, tot.hblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<1>, tail_blocks, ws, L);
         LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<1>, L, ws);
-        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<2>, tot.hblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<2>, tail_blocks, ws, L);
         LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<2>, L, ws);
-        LAUNCH(ADACOMP_KERNEL_COUNT_SEG, k_count, tot.wblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_COUNT_SEG, k_count, tail_blocks, ws, L);
         LAUNCH(ADACOMP_KERNEL_SCAN, k_scan, L, ws);
-        LAUNCH(ADACOMP_KERNEL_EMIT, k_emit, tot.wblk_base, ws, L, out_idx, out_val);
+        LAUNCH(ADACOMP_KERNEL_EMIT, k_emit, tail_blocks, ws, L, out_idx, out_val);
     }
     LAUNCH(ADACOMP_KERNEL_IDENTITY, k_identity, tot.iblk_base, ws, L, out_idx, out_val);
     return ADACOMP_OK;
