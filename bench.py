@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel in one extra untimed step")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the 16 independent selects of a step are spread over (each has its own workspace)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 4 GB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -79,17 +81,34 @@ def main():
     state = ac.State(theta)
     cap = sum(ac.adacomp_count(n, rate) for n in sizes)
     updates = [ac.Update(L, cap, dev) for _ in range(Q)]
-    sel_ws = torch.empty(ac.adacomp_select_workspace(sizes, rate), dtype=torch.uint8, device=dev)
+    ns = max(1, args.streams)
+    streams = [torch.cuda.Stream(device=dev) for _ in range(ns)] if ns > 1 else [torch.cuda.current_stream(dev)]
+    sel_bytes = ac.adacomp_select_workspace(sizes, rate)
+    sel_wss = [torch.empty(sel_bytes, dtype=torch.uint8, device=dev) for _ in range(ns)]
+    sel_ws = sel_wss[0]
     for q in range(Q):      # fills layer_off so that the apply workspace can be sized
         ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
     app_ws = torch.empty(ac.adacomp_apply_workspace(sizes, updates), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
-    def step():
+    main = torch.cuda.current_stream(dev)
+
+    def selects():
+        # the 16 worker updates are independent: spread them over the streams, then join
         t0 = state.t
+        if ns > 1:
+            ready = main.record_event()
+            for st in streams:
+                st.wait_event(ready)        # the previous apply has consumed the update buffers
         for q in range(Q):
             updates[q].pull_ts = t0 + pulls[q]
-            ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
+            ac.adacomp_select(grads[q], rate, updates[q], sel_wss[q % ns], stream=streams[q % ns])
+        if ns > 1:
+            for st in streams:
+                main.wait_event(st.record_event())
+
+    def step():
+        selects()
         ac.adacomp_apply(theta, state, updates, lr, app_ws)
 
     if args.copy_calibration:     # reads 4e9 bytes, writes 4e9 bytes
@@ -132,6 +151,7 @@ def main():
         "config": {"workload": "flat: 100 tensors x 10M fp32 = 1e9 elements per worker gradient, "
                                "95% N(0,1e-5) + 5% N(0,1e-2), rate 0.5% per tensor, 16 queued updates, "
                                "staleness U[1,16]; step = 16 selects + 1 apply of the queue",
+                   "select_streams": ns,
                    "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q},
         "roofline": {"bound": "hbm", "kernel": "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -145,10 +165,7 @@ def main():
     if args.breakdown:
         ac.adacomp_profile_start(None)
     ev[0].record()
-    t0 = state.t
-    for q in range(Q):
-        updates[q].pull_ts = t0 + pulls[q]
-        ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
+    selects()
     ev[1].record()
     ac.adacomp_apply(theta, state, updates, lr, app_ws)
     ev[2].record()
