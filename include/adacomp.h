@@ -44,7 +44,7 @@ enum {
     ADACOMP_ERR_LAYER_MISMATCH = -6,  /* update / state tensor count or sizes differ from params */
     ADACOMP_ERR_FUTURE_PULL = -7,     /* an update's pull_ts is later than its apply time    */
     ADACOMP_ERR_K_RANGE = -8,         /* k_override[l] > n_l                                 */
-    ADACOMP_ERR_HISTORY = -9,         /* pull_ts precedes the first update of this call      */
+    ADACOMP_ERR_HISTORY = -9,         /* pull_ts precedes the oldest remembered update       */
     ADACOMP_ERR_LR = -10,             /* learning rate is not finite                         */
     ADACOMP_ERR_ALIGNMENT = -11,      /* a float/uint32 device pointer is not 4-byte aligned */
     ADACOMP_ERR_HIP = -12             /* a HIP runtime call (kernel launch) failed           */
@@ -87,17 +87,33 @@ typedef struct {
     uint64_t pull_ts;
 } adacomp_update_t;
 
-/* Parameter-server staleness state (Alg. 2; Sec. 4 "Algorithm details": the PS
- * keeps a timestamp and a trace of received updates).  Caller-owned memory whose
- * contents the library defines; zero-initialise for a fresh server.
- *   t     i: number of updates applied so far (advanced by adacomp_apply)
- *   cnt   HOST array [num_layers] of DEVICE pointers; cnt[l][k] (uint32, n_l of
- *         them) = number of applied updates whose entry for parameter k of tensor l
- *         was non-zero.  sigma_k of eq. 3 is a difference of two readings of it. */
+/* Parameter-server staleness state (Alg. 2; Sec. 4 "Algorithm details": the PS keeps a
+ * timestamp and a trace of received updates).  Caller-owned memory whose contents the
+ * library defines; zero-initialise t, history_len and cnt[][] for a fresh server.
+ *   t            i: number of updates applied so far (advanced by adacomp_apply)
+ *   cnt          HOST array [num_layers] of DEVICE pointers; cnt[l][k] (uint32, n_l of
+ *                them) = number of applied updates whose entry for parameter k of tensor
+ *                l was non-zero.  Inside one adacomp_apply call sigma_k of eq. 3 is a
+ *                difference of two readings of it.
+ *   history_cap  d: how many applied updates the trace remembers (Sec. 4 "Complexity":
+ *                the last d updates, d = the worst delay); 0 = none
+ *   history_len  remembered so far (maintained by adacomp_apply)
+ *   history      HOST ring [history_cap], maintained by adacomp_apply: slot (u mod
+ *                history_cap) describes applied update u.  Only descriptors are kept: the
+ *                DEVICE buffers idx/val/layer_off_dev of an applied update must stay
+ *                allocated and unchanged until history_cap later updates have been
+ *                applied and their stream work has finished
+ *   history_off  HOST [history_cap * (num_layers + 1)], maintained by adacomp_apply
+ *                (copies of the remembered updates' layer_off)
+ * With history_cap = 0, history and history_off may be NULL. */
 typedef struct {
     uint64_t t;
     uint32_t num_layers;
     uint32_t **cnt;
+    uint32_t history_cap;
+    uint32_t history_len;
+    adacomp_update_t *history;
+    uint64_t *history_off;
 } adacomp_state_t;
 
 /* k_l: how many entries "(100*c)%" of an n-entry tensor means (Alg. 1,
@@ -133,11 +149,13 @@ int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double rate,
                    const uint64_t *k_override, adacomp_update_t *out,
                    void *workspace, size_t ws_bytes, void *hip_stream);
 
-/* Bytes of DEVICE workspace adacomp_apply needs for a queue of Q updates (HOST
- * array; only num_layers and layer_off are read) on L parameter tensors of sizes
- * n[0..L) (HOST).  Depends on these sizes only. */
-int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
-                            uint32_t Q, size_t *bytes);
+/* Bytes of DEVICE workspace adacomp_apply needs for a queue of Q updates (HOST array;
+ * num_layers, layer_off and pull_ts are read) on L parameter tensors of sizes n[0..L)
+ * (HOST), applied to state st (HOST; only t and the history fields are read; NULL = a
+ * fresh state).  Depends on these sizes and timestamps only.  Returns the same timestamp
+ * errors as adacomp_apply would. */
+int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_state_t *st,
+                            const adacomp_update_t *updates, uint32_t Q, size_t *bytes);
 
 /* Parameter-server iterations (Alg. 2, loop body) for a queue: updates[0..Q) are
  * applied in array order as iterations i = st->t, st->t + 1, ...; for each entry
@@ -152,8 +170,12 @@ int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_update_
  *   st       HOST struct; st->num_layers == L; st->cnt HOST [L] of DEVICE pointers
  *   updates  HOST [Q]; each must have num_layers == L, idx < n_l, strictly ascending
  *            per tensor (malformed index lists are undefined behaviour);
- *            st->t <= pull_ts <= apply time of that update, else
- *            ADACOMP_ERR_HISTORY / ADACOMP_ERR_FUTURE_PULL
+ *            pull_ts <= apply time of that update (else ADACOMP_ERR_FUTURE_PULL) and
+ *            pull_ts >= st->t - (remembered updates) (else ADACOMP_ERR_HISTORY): an
+ *            update pulled before this call has the earlier part of its window
+ *            searched in the remembered updates' sorted index lists, by bisection, as
+ *            Sec. 4 "Complexity" describes; with history_cap = 0 every pull_ts must be
+ *            >= st->t
  *   lr       alpha, finite
  *   workspace DEVICE, 256-byte aligned, >= adacomp_apply_workspace() bytes
  * The queue is executed either update by update (scatter) or in one sweep over
@@ -184,6 +206,7 @@ enum {
     ADACOMP_KERNEL_SCAN,           /* select: exclusive scan of the segment counts              */
     ADACOMP_KERNEL_EMIT,           /* select: ordered write of the (index, value) pairs         */
     ADACOMP_KERNEL_IDENTITY,       /* select: k == n copy                                       */
+    ADACOMP_KERNEL_HISTORY,        /* apply: staleness accumulated before the call (bisection)  */
     ADACOMP_KERNEL_SNAPSHOT,       /* apply: counter reading at pull time                       */
     ADACOMP_KERNEL_SCATTER_APPLY,  /* apply: eqs. 3-5 scatter, one update                       */
     ADACOMP_KERNEL_BOUNDS,         /* apply: slice of every update per coordinate tile          */

@@ -35,7 +35,9 @@ class _Update(C.Structure):
 
 
 class _State(C.Structure):
-    _fields_ = [("t", C.c_uint64), ("num_layers", C.c_uint32), ("cnt", C.POINTER(C.c_void_p))]
+    _fields_ = [("t", C.c_uint64), ("num_layers", C.c_uint32), ("cnt", C.POINTER(C.c_void_p)),
+                ("history_cap", C.c_uint32), ("history_len", C.c_uint32),
+                ("history", C.POINTER(_Update)), ("history_off", C.POINTER(C.c_uint64))]
 
 
 def library_path():
@@ -61,7 +63,8 @@ def load_library():
     lib.adacomp_select.argtypes = [C.POINTER(_Layer), u32, C.c_double, C.POINTER(u64), C.POINTER(_Update),
                                    vp, sz, vp]
     lib.adacomp_apply_workspace.restype = C.c_int
-    lib.adacomp_apply_workspace.argtypes = [C.POINTER(u64), u32, C.POINTER(_Update), u32, C.POINTER(sz)]
+    lib.adacomp_apply_workspace.argtypes = [C.POINTER(u64), u32, C.POINTER(_State), C.POINTER(_Update), u32,
+                                            C.POINTER(sz)]
     lib.adacomp_apply.restype = C.c_int
     lib.adacomp_apply.argtypes = [C.POINTER(_Layer), u32, C.POINTER(_State), C.POINTER(_Update), u32,
                                   C.c_float, vp, sz, vp]
@@ -128,12 +131,21 @@ class Update:
 
 
 class State:
-    """Parameter-server staleness state (adacomp_state_t): timestamp and per-parameter counters."""
+    """Parameter-server staleness state (adacomp_state_t): timestamp, per-parameter counters and,
+    with history > 0, the ring of descriptors of the last `history` applied updates.  The State
+    keeps the remembered Update objects referenced so that their device buffers stay alive."""
 
-    def __init__(self, params):
+    def __init__(self, params, history=0):
+        L = len(params)
         self.cnt = [torch.zeros(max(p.numel(), 1), dtype=torch.int32, device=p.device) for p in params]
-        self._cnt_ptrs = (C.c_void_p * max(len(params), 1))(*[c.data_ptr() for c in self.cnt])
-        self._c = _State(0, len(params), C.cast(self._cnt_ptrs, C.POINTER(C.c_void_p)))
+        self._cnt_ptrs = (C.c_void_p * max(L, 1))(*[c.data_ptr() for c in self.cnt])
+        self.history_cap = int(history)
+        self._ring = (_Update * max(self.history_cap, 1))()
+        self._ring_off = (C.c_uint64 * max(self.history_cap * (L + 1), 1))()
+        self._keep = {}
+        self._c = _State(0, L, C.cast(self._cnt_ptrs, C.POINTER(C.c_void_p)), self.history_cap, 0,
+                         C.cast(self._ring, C.POINTER(_Update)) if self.history_cap else None,
+                         C.cast(self._ring_off, C.POINTER(C.c_uint64)) if self.history_cap else None)
 
     @property
     def t(self):
@@ -142,6 +154,11 @@ class State:
     @t.setter
     def t(self, v):
         self._c.t = int(v)
+
+    def _remember(self, t0, updates):
+        if self.history_cap:
+            for q, u in enumerate(updates):
+                self._keep[(t0 + q) % self.history_cap] = u
 
 
 def adacomp_strerror(code):
@@ -184,11 +201,14 @@ def adacomp_select(layers, rate, out, workspace, k_override=None, stream=None):
     return out
 
 
-def adacomp_apply_workspace(sizes, updates):
-    """Workspace bytes for applying `updates` to parameter tensors of the given sizes."""
+def adacomp_apply_workspace(sizes, updates, state=None):
+    """Workspace bytes for applying `updates` to parameter tensors of the given sizes (state:
+    the State they will be applied to; None = a fresh one)."""
     out = C.c_size_t(0)
     arr = (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
-    rc = load_library().adacomp_apply_workspace(_u64_array(sizes), len(sizes), arr, len(updates), C.byref(out))
+    rc = load_library().adacomp_apply_workspace(_u64_array(sizes), len(sizes),
+                                                C.byref(state._c) if state is not None else None,
+                                                arr, len(updates), C.byref(out))
     if rc:
         raise AdaCompError(rc, "adacomp_apply_workspace")
     return int(out.value)
@@ -203,10 +223,11 @@ def adacomp_apply(params, state, updates, lr, workspace, stream=None):
                                       workspace.numel() * workspace.element_size(), _stream_ptr(stream, dev))
     if rc:
         raise AdaCompError(rc, "adacomp_apply")
+    state._remember(state.t - len(updates), updates)
     return state
 
 
-KERNEL_COUNT = 19
+KERNEL_COUNT = 20
 
 
 def adacomp_kernel_name(kernel_id):

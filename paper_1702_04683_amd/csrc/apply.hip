@@ -59,7 +59,8 @@ struct UpdDesc {
     const float *val;
     const uint64_t *off;  // layer_off_dev
     uint32_t *snap;       // scratch: counter readings at pull time, one per entry
-    uint32_t pull;        // pull timestamp relative to the first update of the call
+    const uint32_t *pre;  // staleness already accumulated before this call (pulled earlier), or nullptr
+    uint32_t pull;        // pull timestamp relative to the first update of the call (0 if pulled earlier)
     uint32_t pad;
 };
 static_assert(sizeof(UpdDesc) % 8 == 0, "table is uploaded as 64-bit words");
@@ -74,6 +75,15 @@ __device__ __forceinline__ float step(float theta, float lr, uint32_t sigma, flo
 __device__ __forceinline__ bool is_nonzero(float v) {  // indicator of eq. 3
     return (__float_as_uint(v) & KEY_MASK) != 0;
 }
+
+// An update applied by an earlier call, as the trace of Sec. 4 "Complexity" keeps it: its
+// sorted index lists (and values, for the non-zero test of eq. 3).
+struct HistDesc {
+    const uint32_t *idx;
+    const float *val;
+    const uint64_t *off;  // layer_off_dev
+};
+static_assert(sizeof(HistDesc) % 8 == 0, "table is uploaded as 64-bit words");
 
 // ------------------------------------------------------------------ scatter plan
 
@@ -101,12 +111,41 @@ __global__ __launch_bounds__(BLOCK) void k_snapshot(const ParamDesc *P, uint32_t
     }
 }
 
-// One PS iteration.  STALE: the update was pulled two or more iterations ago and has a
-// snapshot; otherwise sigma_k is 0 or 1 for every entry and alpha_k = alpha.
-template <bool STALE>
+// The part of eq. 3 that lies before the current call: for every entry of an update pulled
+// at an earlier timestamp, the number of remembered updates H[first..nh) (= timestamps pull ..
+// t0-1) that hold a non-zero entry for the same parameter, by bisection in their sorted
+// index lists -- the search the paper describes (Sec. 4 "Complexity").
+__global__ __launch_bounds__(BLOCK) void k_history(const HistDesc *H, uint32_t first, uint32_t nh, uint32_t L,
+                                                   const uint64_t *off, const uint32_t *idx, uint32_t *pre,
+                                                   uint64_t total) {
+    const uint64_t e = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (e >= total) return;
+    const uint32_t l = layer_of(off, L, e);
+    const uint32_t k = idx[e];
+    uint32_t sigma = 0;
+    for (uint32_t h = first; h < nh; ++h) {
+        const HistDesc u = H[h];
+        if (!u.off) continue;  // an empty update was applied at that timestamp
+        uint64_t lo = u.off[l], hi = u.off[l + 1];
+        const uint64_t end = hi;
+        while (lo < hi) {
+            const uint64_t mid = lo + ((hi - lo) >> 1);
+            if (u.idx[mid] < k) lo = mid + 1; else hi = mid;
+        }
+        if (lo < end && u.idx[lo] == k && is_nonzero(u.val[lo])) ++sigma;
+    }
+    pre[e] = sigma;
+}
+
+// One PS iteration.  STALE: the update has a snapshot of the counters taken at its pull time
+// (or at the start of the call if it was pulled earlier); PRE: it was pulled before this call
+// and carries the staleness accumulated until the call.  Without either, sigma_k is 0 or 1
+// for every entry and alpha_k = alpha.
+template <bool STALE, bool PRE>
 __global__ __launch_bounds__(BLOCK) void k_scatter_apply(const ParamDesc *P, uint32_t L, const uint64_t *off,
                                                          const uint32_t *idx, const float *val,
-                                                         const uint32_t *snap, uint64_t total, float lr) {
+                                                         const uint32_t *snap, const uint32_t *pre, uint64_t total,
+                                                         float lr) {
     uint64_t e = (uint64_t)blockIdx.x * (BLOCK * ITEMS) + threadIdx.x;
     if (e >= total) return;
     uint32_t l = layer_of(off, L, e);
@@ -121,7 +160,8 @@ __global__ __launch_bounds__(BLOCK) void k_scatter_apply(const ParamDesc *P, uin
         uint32_t *cnt = P[l].cnt + k;
         uint32_t c = 0, sigma = 0;
         if (STALE || nonzero) c = *cnt;
-        if (STALE) sigma = c - snap[e];  // eq. 3
+        if (STALE) sigma = c - snap[e];  // eq. 3, the part inside this call
+        if (PRE) sigma += pre[e];        // eq. 3, the part before it
         *theta = step(*theta, lr, sigma, v);
         if (nonzero) *cnt = c + 1;
     }
@@ -179,7 +219,8 @@ struct Slices {
     uint32_t b0[PASS];           // its entry number inside the update
     const uint32_t *idx[PASS];   // the update's arrays
     const float *val[PASS];
-    uint32_t tag[PASS];          // update number | staleness << 15 (key bits of its touches)
+    const uint32_t *pre[PASS];   // staleness accumulated before the call, per entry, or nullptr
+    uint32_t tag[PASS];          // update number | staleness inside the call << 15 (key bits of its touches)
 };
 
 __device__ __forceinline__ uint32_t load_slices(const Sweep &sw, uint32_t t, uint32_t q0, Slices &sl,
@@ -194,6 +235,7 @@ __device__ __forceinline__ uint32_t load_slices(const Sweep &sw, uint32_t t, uin
         len = row[1] - b0;
         sl.idx[threadIdx.x] = u.idx;
         sl.val[threadIdx.x] = u.val;
+        sl.pre[threadIdx.x] = u.pre;
         sl.tag[threadIdx.x] = q | ((q - u.pull) << 15);
     }
     uint32_t total;
@@ -218,8 +260,11 @@ constexpr uint32_t PER_THREAD = STAGE_CAP / BLOCK;  // staged entries per thread
 
 __device__ __forceinline__ uint32_t slot(uint32_t c) { return c + (c >> 4); }
 
-// A touch in LDS: key = update number (15 bits) | its global staleness q - pull (15 bits,
-// from bit 15) | value-is-non-zero (bit 31); value separately.
+// A touch in LDS: key = update number (15 bits) | staleness field (15 bits, from bit 15) |
+// pulled-before-the-call (bit 30) | value-is-non-zero (bit 31); value separately.  The
+// staleness field is q - pull for an update pulled inside the call; for one pulled earlier
+// its window covers the whole call so far, and the field holds the staleness it had
+// accumulated before the call.
 __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
     // per coordinate: count, then start, then end of its list; slot(c) skews the index so
     // that the scan's 16-consecutive-per-thread accesses fall into distinct banks
@@ -264,6 +309,11 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
                 c[j] = sl.idx[i][e] - c0;
                 v[j] = sl.val[i][e];
                 key[j] = sl.tag[i];
+                if (sl.pre[i]) {
+                    const uint32_t before = sl.pre[i][e];
+                    if (before > 0x7fffu) s_bad = 1;  // does not fit the key: leave the tile to the slow kernel
+                    key[j] = (key[j] & 0x7fffu) | (before << 15) | 0x40000000u;
+                }
             }
         }
 #pragma unroll
@@ -309,6 +359,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
                     c[j] = sl.idx[i][e] - c0;
                     v[j] = sl.val[i][e];
                     key[j] = sl.tag[i];
+                    if (sl.pre[i]) key[j] = (key[j] & 0x7fffu) | (sl.pre[i][e] << 15) | 0x40000000u;
                 }
             }
         }
@@ -336,9 +387,11 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
         if (x >= total) continue;
         const uint32_t kx = s_key[x], cx = s_coord[x];
         const uint32_t qx = kx & 0x7fffu;
-        const uint32_t pull = qx - ((kx >> 15) & 0x7fffu);
+        const bool earlier = (kx >> 30) & 1u;  // pulled before the call
+        const uint32_t field = (kx >> 15) & 0x7fffu;
+        const uint32_t pull = earlier ? 0u : qx - field;
         const uint32_t beg = cx ? s_cur[slot(cx - 1)] : 0u, end = s_cur[slot(cx)];
-        uint32_t rank = 0, sigma = 0;
+        uint32_t rank = 0, sigma = earlier ? field : 0u;
         for (uint32_t y = beg; y < end; ++y) {
             const uint32_t ky = s_key[y];
             const uint32_t qy = ky & 0x7fffu;
@@ -389,12 +442,12 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
             __syncthreads();
             const UpdDesc u = sw.U[q];
             const uint32_t *row = sw.B + (uint64_t)q * (sw.ntiles + 1) + t;
-            const bool stale = q - u.pull >= 2;
+            const bool stale = q - u.pull >= (u.pre ? 1u : 2u);  // has a snapshot (host: same rule)
             for (uint32_t e = row[0] + threadIdx.x; e < row[1]; e += BLOCK) {
                 const uint32_t k = u.idx[e];
                 const float v = u.val[e];
                 const uint32_t c = pd.cnt[k];
-                const uint32_t sigma = stale ? c - u.snap[e] : 0u;
+                const uint32_t sigma = (stale ? c - u.snap[e] : 0u) + (u.pre ? u.pre[e] : 0u);
                 pd.theta[k] = step(pd.theta[k], sw.lr, sigma, v);
                 if (is_nonzero(v)) pd.cnt[k] = c + 1;
             }
@@ -409,8 +462,10 @@ struct Layout {
     bool sweep = false;
     uint32_t tile_shift = 0;
     uint64_t ntiles = 0;
-    size_t table = 0, upd = 0, pa_off = 0, pa_list = 0, bounds = 0, tile_tensor = 0, ovf = 0;
+    uint32_t n_hist = 0;  // remembered updates this call reaches back to
+    size_t table = 0, upd = 0, pa_off = 0, pa_list = 0, bounds = 0, tile_tensor = 0, ovf = 0, hist = 0;
     std::vector<size_t> snap;  // byte offset per update
+    std::vector<size_t> pre;   // byte offset per update pulled before the call, else SIZE_MAX
     size_t bytes = 0;
 };
 
@@ -427,15 +482,36 @@ int check_updates(uint32_t L, const adacomp_update_t *updates, uint32_t Q) {
     return ADACOMP_OK;
 }
 
-// Plan and workspace layout from sizes alone.  The sweep pays 16 bytes per parameter plus
-// about 30 per entry; the scatter about 440 bytes per entry (measured line traffic).
-void make_layout(const uint64_t *n, uint32_t L, const adacomp_update_t *updates, uint32_t Q, Layout &lay) {
+// Timestamps against the state: every update must have been pulled no later than it is
+// applied and no earlier than the oldest remembered update.
+int check_pulls(const adacomp_state_t *st, const adacomp_update_t *updates, uint32_t Q) {
+    const uint64_t t0 = st ? st->t : 0;
+    uint64_t remembered = 0;
+    if (st && st->history_cap) {
+        if (!st->history || !st->history_off) return ADACOMP_ERR_NULL;
+        remembered = st->history_len < st->history_cap ? st->history_len : st->history_cap;
+        if (remembered > t0) remembered = t0;
+    }
+    for (uint32_t q = 0; q < Q; ++q) {
+        if (updates[q].pull_ts > t0 + q) return ADACOMP_ERR_FUTURE_PULL;
+        if (updates[q].pull_ts + remembered < t0) return ADACOMP_ERR_HISTORY;
+    }
+    return ADACOMP_OK;
+}
+
+// Plan and workspace layout from sizes and timestamps alone.  The sweep pays 16 bytes per
+// parameter plus about 30 per entry; the scatter about 440 bytes per entry (measured line traffic).
+void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_update_t *updates, uint32_t Q,
+                 Layout &lay) {
     double entries = 0, params = 0;
     bool fits32 = true;
+    uint64_t oldest = t0;
     for (uint32_t q = 0; q < Q; ++q) {
         entries += (double)updates[q].layer_off[L];
         fits32 = fits32 && updates[q].layer_off[L] <= 0xffffffffull;
+        if (updates[q].pull_ts < oldest && updates[q].layer_off[L] > 0) oldest = updates[q].pull_ts;
     }
+    lay.n_hist = (uint32_t)(t0 - oldest);
     for (uint32_t l = 0; l < L; ++l) params += (double)n[l];
     // ADACOMP_APPLY_PLAN=scatter|sweep overrides the cost model (for tests and measurements)
     const char *force = std::getenv("ADACOMP_APPLY_PLAN");
@@ -463,6 +539,7 @@ void make_layout(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
         return at;
     };
     lay.table = take(((size_t)L + 1) * sizeof(ParamDesc));
+    lay.hist = take((size_t)lay.n_hist * sizeof(HistDesc));
     if (lay.sweep) {
         lay.upd = take((size_t)Q * sizeof(UpdDesc));
         lay.pa_off = take(((size_t)Q + 1) * sizeof(uint32_t));
@@ -472,7 +549,12 @@ void make_layout(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
         lay.ovf = take((lay.ntiles + 1) * sizeof(uint32_t));
     }
     lay.snap.resize(Q);
-    for (uint32_t q = 0; q < Q; ++q) lay.snap[q] = take((size_t)updates[q].layer_off[L] * sizeof(uint32_t));
+    lay.pre.assign(Q, SIZE_MAX);
+    for (uint32_t q = 0; q < Q; ++q) {
+        lay.snap[q] = take((size_t)updates[q].layer_off[L] * sizeof(uint32_t));
+        if (updates[q].pull_ts < t0 && updates[q].layer_off[L] > 0)
+            lay.pre[q] = take((size_t)updates[q].layer_off[L] * sizeof(uint32_t));
+    }
     lay.bytes = off;
 }
 
@@ -481,13 +563,15 @@ void make_layout(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
 
 using namespace adacomp;
 
-extern "C" int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_update_t *updates,
-                                       uint32_t Q, size_t *bytes) {
+extern "C" int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_state_t *st,
+                                       const adacomp_update_t *updates, uint32_t Q, size_t *bytes) {
     if (!bytes || (L && !n)) return ADACOMP_ERR_NULL;
     int rc = check_updates(L, updates, Q);
     if (rc) return rc;
+    rc = check_pulls(st, updates, Q);
+    if (rc) return rc;
     Layout lay;
-    make_layout(n, L, updates, Q, lay);
+    make_layout(n, L, st ? st->t : 0, updates, Q, lay);
     *bytes = lay.bytes;
     return ADACOMP_OK;
 }
@@ -525,11 +609,11 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         if (total && (!u.idx || !u.val || !u.layer_off_dev)) return ADACOMP_ERR_NULL;
         if (((uintptr_t)u.idx & 3u) || ((uintptr_t)u.val & 3u) || ((uintptr_t)u.layer_off_dev & 7u))
             return ADACOMP_ERR_ALIGNMENT;
-        if (u.pull_ts > t0 + q) return ADACOMP_ERR_FUTURE_PULL;
-        if (u.pull_ts < t0) return ADACOMP_ERR_HISTORY;
     }
+    rc = check_pulls(st, updates, Q);
+    if (rc) return rc;
     Layout lay;
-    make_layout(n.data(), L, updates, Q, lay);
+    make_layout(n.data(), L, t0, updates, Q, lay);
     if (!workspace || ((uintptr_t)workspace & 255u) || ws_bytes < lay.bytes) return ADACOMP_ERR_WORKSPACE;
     if (Q == 0) return ADACOMP_OK;
 
@@ -537,18 +621,47 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
     char *wsb = static_cast<char *>(workspace);
     ParamDesc *P = reinterpret_cast<ParamDesc *>(wsb + lay.table);
 
-    // pulled_at[q]: updates whose worker pulled at PS time t0 + q and that arrive two
-    // or more iterations later (Alg. 1 "Pull" / Alg. 2 "Get"): their counters are
-    // read just before update q is applied.
-    std::vector<std::vector<uint32_t>> pulled_at(Q);
-    std::vector<char> stale(Q, 0);
-    for (uint32_t q = 0; q < Q; ++q) {
-        const uint64_t j = updates[q].pull_ts - t0;
-        if (q - j >= 2 && updates[q].layer_off[L] > 0) {
-            stale[q] = 1;
-            pulled_at[j].push_back(q);
+    // Staleness accumulated before this call (eq. 3, u = pull .. t0-1) for the updates that
+    // were pulled earlier: searched in the remembered updates t0 - n_hist .. t0 - 1.
+    if (lay.n_hist) {
+        std::vector<HistDesc> hist(lay.n_hist);
+        for (uint32_t h = 0; h < lay.n_hist; ++h) {
+            const adacomp_update_t &u = st->history[(t0 - lay.n_hist + h) % st->history_cap];
+            hist[h] = u.layer_off[L] ? HistDesc{u.idx, u.val, u.layer_off_dev} : HistDesc{nullptr, nullptr, nullptr};
+        }
+        const HistDesc *H = reinterpret_cast<const HistDesc *>(wsb + lay.hist);
+        if (put_async(wsb + lay.hist, hist.data(), hist.size() * sizeof(HistDesc), s) != hipSuccess)
+            return ADACOMP_ERR_HIP;
+        for (uint32_t q = 0; q < Q; ++q) {
+            if (lay.pre[q] == SIZE_MAX) continue;
+            const adacomp_update_t &u = updates[q];
+            const uint64_t total = u.layer_off[L];
+            const uint32_t first = lay.n_hist - (uint32_t)(t0 - u.pull_ts);
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_HISTORY, k_history, dim3((unsigned)((total + BLOCK - 1) / BLOCK)),
+                           dim3(BLOCK), s, H, first, lay.n_hist, L, u.layer_off_dev, u.idx,
+                           reinterpret_cast<uint32_t *>(wsb + lay.pre[q]), total);
+            CHECK_LAUNCH();
         }
     }
+
+    // Inside the call an update pulled earlier behaves as if pulled at the call's first
+    // timestamp.  pulled_at[q]: updates whose counters are read just before update q is
+    // applied (Alg. 1 "Pull" / Alg. 2 "Get").  A snapshot is needed when the window inside
+    // the call can change alpha: two or more iterations, or one on top of earlier staleness.
+    std::vector<std::vector<uint32_t>> pulled_at(Q);
+    std::vector<char> stale(Q, 0);
+    std::vector<uint32_t> pull_rel(Q);
+    for (uint32_t q = 0; q < Q; ++q) {
+        const bool earlier = updates[q].pull_ts < t0;
+        pull_rel[q] = earlier ? 0u : (uint32_t)(updates[q].pull_ts - t0);
+        if (updates[q].layer_off[L] > 0 && q - pull_rel[q] >= (lay.pre[q] != SIZE_MAX ? 1u : 2u)) {
+            stale[q] = 1;
+            pulled_at[pull_rel[q]].push_back(q);
+        }
+    }
+    auto pre_of = [&](uint32_t q) {
+        return lay.pre[q] == SIZE_MAX ? nullptr : reinterpret_cast<const uint32_t *>(wsb + lay.pre[q]);
+    };
 
     if (lay.sweep) {
         uint64_t tiles = 0;
@@ -562,7 +675,7 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         for (uint32_t q = 0; q < Q; ++q) {
             const adacomp_update_t &u = updates[q];
             upd[q] = UpdDesc{u.idx, u.val, u.layer_off_dev, reinterpret_cast<uint32_t *>(wsb + lay.snap[q]),
-                             (uint32_t)(u.pull_ts - t0), 0};
+                             pre_of(q), pull_rel[q], 0};
             pa_off[q] = (uint32_t)pa_list.size();
             pa_list.insert(pa_list.end(), pulled_at[q].begin(), pulled_at[q].end());
         }
@@ -598,33 +711,48 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP_SLOW, k_sweep_slow,
                        dim3((unsigned)std::min<uint64_t>(lay.ntiles, SLOW_GRID)), dim3(BLOCK), s, sw);
         CHECK_LAUNCH();
-        st->t = t0 + Q;
-        return ADACOMP_OK;
-    }
-
-    if (L && put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess)
-        return ADACOMP_ERR_HIP;
-    for (uint32_t q = 0; q < Q; ++q) {
-        for (uint32_t w : pulled_at[q]) {
-            const adacomp_update_t &u = updates[w];
+    } else {
+        if (L && put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess)
+            return ADACOMP_ERR_HIP;
+        for (uint32_t q = 0; q < Q; ++q) {
+            for (uint32_t w : pulled_at[q]) {
+                const adacomp_update_t &u = updates[w];
+                const uint64_t total = u.layer_off[L];
+                const unsigned grid = (unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS));
+                ADACOMP_LAUNCH(ADACOMP_KERNEL_SNAPSHOT, k_snapshot, dim3(grid), dim3(BLOCK), s, P, L,
+                               u.layer_off_dev, u.idx, reinterpret_cast<uint32_t *>(wsb + lay.snap[w]), total);
+                CHECK_LAUNCH();
+            }
+            const adacomp_update_t &u = updates[q];
             const uint64_t total = u.layer_off[L];
-            const unsigned grid = (unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS));
-            ADACOMP_LAUNCH(ADACOMP_KERNEL_SNAPSHOT, k_snapshot, dim3(grid), dim3(BLOCK), s, P, L,
-                           u.layer_off_dev, u.idx, reinterpret_cast<uint32_t *>(wsb + lay.snap[w]), total);
+            if (total == 0) continue;  // an empty push only advances the timestamp
+            const dim3 grid((unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS)));
+            const uint32_t *snap = reinterpret_cast<const uint32_t *>(wsb + lay.snap[q]);
+            const uint32_t *pre = pre_of(q);
+#define SCATTER(STALE, PRE)                                                                                       \
+    ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, (k_scatter_apply<STALE, PRE>), grid, dim3(BLOCK), s, P, L,       \
+                   u.layer_off_dev, u.idx, u.val, snap, pre, total, lr)
+            if (stale[q] && pre) SCATTER(true, true);
+            else if (stale[q]) SCATTER(true, false);
+            else if (pre) SCATTER(false, true);
+            else SCATTER(false, false);
+#undef SCATTER
             CHECK_LAUNCH();
         }
-        const adacomp_update_t &u = updates[q];
-        const uint64_t total = u.layer_off[L];
-        if (total == 0) continue;  // an empty push only advances the timestamp
-        const unsigned grid = (unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS));
-        const uint32_t *snap = reinterpret_cast<const uint32_t *>(wsb + lay.snap[q]);
-        if (stale[q])
-            ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, k_scatter_apply<true>, dim3(grid), dim3(BLOCK), s, P, L,
-                           u.layer_off_dev, u.idx, u.val, snap, total, lr);
-        else
-            ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, k_scatter_apply<false>, dim3(grid), dim3(BLOCK), s, P, L,
-                           u.layer_off_dev, u.idx, u.val, snap, total, lr);
-        CHECK_LAUNCH();
+    }
+
+    // remember the applied updates: slot (timestamp mod history_cap) of the trace
+    if (st->history_cap) {
+        const uint32_t first = Q > st->history_cap ? Q - st->history_cap : 0;
+        for (uint32_t q = first; q < Q; ++q) {
+            const uint64_t slot = (t0 + q) % st->history_cap;
+            uint64_t *off = st->history_off + slot * ((uint64_t)L + 1);
+            std::memcpy(off, updates[q].layer_off, ((size_t)L + 1) * sizeof(uint64_t));
+            st->history[slot] = updates[q];
+            st->history[slot].layer_off = off;
+        }
+        const uint64_t len = (uint64_t)st->history_len + Q;
+        st->history_len = (uint32_t)(len < st->history_cap ? len : st->history_cap);
     }
     st->t = t0 + Q;
     return ADACOMP_OK;

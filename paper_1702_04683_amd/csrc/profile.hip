@@ -93,6 +93,7 @@ extern "C" const char *adacomp_kernel_name(int id) {
         case ADACOMP_KERNEL_SCAN: return "scan";
         case ADACOMP_KERNEL_EMIT: return "emit";
         case ADACOMP_KERNEL_IDENTITY: return "identity";
+        case ADACOMP_KERNEL_HISTORY: return "history";
         case ADACOMP_KERNEL_SNAPSHOT: return "snapshot";
         case ADACOMP_KERNEL_SCATTER_APPLY: return "scatter_apply";
         case ADACOMP_KERNEL_BOUNDS: return "bounds";

@@ -1019,7 +1019,7 @@ extern "C" const char *adacomp_strerror(int code) {
         case ADACOMP_ERR_LAYER_MISMATCH: return "tensor count or sizes of update/state differ from the parameters";
         case ADACOMP_ERR_FUTURE_PULL: return "an update was pulled after the time it is applied";
         case ADACOMP_ERR_K_RANGE: return "k_override exceeds the tensor size";
-        case ADACOMP_ERR_HISTORY: return "an update was pulled before the first update of this call";
+        case ADACOMP_ERR_HISTORY: return "an update was pulled before the oldest remembered update";
         case ADACOMP_ERR_LR: return "learning rate is not finite";
         case ADACOMP_ERR_ALIGNMENT: return "a device pointer is not aligned to its element size";
         case ADACOMP_ERR_HIP: return "a HIP runtime call failed";

@@ -128,4 +128,15 @@ def test_apply_argument_checks_run_before_any_launch(lib):
     assert st.t == 5                                        # no failing call advanced the timestamp
     need = C.c_size_t()
     n = (C.c_uint64 * 1)(100)
-    assert lib.adacomp_apply_workspace(n, 1, upd, 1, C.byref(need)) == 0 and need.value >= 12
+    assert lib.adacomp_apply_workspace(n, 1, C.byref(st), upd, 1, C.byref(need)) == 0 and need.value >= 12
+    upd[0].pull_ts = 3                                      # two timestamps back, nothing remembered
+    assert lib.adacomp_apply_workspace(n, 1, C.byref(st), upd, 1, C.byref(need)) == -9
+    ring = (binding._Update * 4)()
+    ring_off = (C.c_uint64 * 8)()
+    st.history_cap, st.history_len = 4, 1
+    st.history, st.history_off = C.cast(ring, C.POINTER(binding._Update)), C.cast(ring_off, C.POINTER(C.c_uint64))
+    assert call() == -9                                     # only one update remembered
+    st.history_len = 2
+    upd[0].pull_ts = 6
+    assert call() == -7
+    assert lib.adacomp_apply_workspace(n, 1, None, upd, 1, C.byref(need)) == -7

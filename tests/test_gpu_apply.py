@@ -29,17 +29,17 @@ def dev():
     return torch.device("cuda:0")
 
 
-def run_gpu(ac, theta_host, updates_host, pulls, lr, dev, chunks=None, state=None):
+def run_gpu(ac, theta_host, updates_host, pulls, lr, dev, chunks=None, state=None, history=0):
     """updates_host: list of (off, idx, val).  Returns (theta list of numpy, counters, state)."""
     theta = [torch.from_numpy(t.copy()).to(dev) for t in theta_host]
     L = len(theta)
     ups = [ac.Update.from_host(o, i, v, dev, pull_ts=p) for (o, i, v), p in zip(updates_host, pulls)]
-    st = ac.State(theta) if state is None else state
+    st = ac.State(theta, history=history) if state is None else state
     chunks = chunks or [len(ups)]
     pos = 0
     for c in chunks:
         part = ups[pos:pos + c]
-        ws = torch.empty(max(ac.adacomp_apply_workspace([t.numel() for t in theta], part), 256), dtype=torch.uint8, device=dev)
+        ws = torch.empty(max(ac.adacomp_apply_workspace([t.numel() for t in theta], part, st), 256), dtype=torch.uint8, device=dev)
         ac.adacomp_apply(theta, st, part, lr, ws)
         pos += c
     torch.cuda.synchronize()
@@ -338,3 +338,75 @@ def test_sweep_and_scatter_agree_on_cnn_queue_bitwise(ac, dev, monkeypatch):
         assert np.array_equal(a, b)
     want = run_oracle(theta0, ups, pulls, 0.01, method=oracle.HISTORY_BITMAP)
     assert compare(res["sweep"][0], want, "cnn queue, sweep") == 0
+
+
+@pytest.mark.parametrize("plan", ["scatter", "sweep", "auto"])
+def test_pulls_reaching_back_across_calls(ac, dev, plan, monkeypatch):
+    """The parameter server of Alg. 2 receives updates a few at a time; a worker may have pulled
+    long before the current call.  With a trace of the last d updates the earlier part of the
+    window of eq. 3 is searched in the remembered index lists; the result must be the oracle's,
+    whatever the split into calls."""
+    if plan != "auto":
+        monkeypatch.setenv("ADACOMP_APPLY_PLAN", plan)
+    rng = np.random.default_rng(31)
+    d = 16
+    for trial, (sizes, Q, density) in enumerate([([4000, 37, 1], 70, 0.05), ([700], 50, 0.4), ([30_000, 5], 40, 0.01)]):
+        ups = random_updates(rng, sizes, Q, density, zero_frac=0.1)
+        ups[5] = (np.zeros(len(sizes) + 1, dtype=np.uint64), np.empty(0, np.uint32), np.empty(0, np.float32))
+        pulls = [int(rng.integers(max(0, q - d), q + 1)) for q in range(Q)]
+        chunks = []
+        while sum(chunks) < Q:
+            chunks.append(min(int(rng.integers(1, 8)), Q - sum(chunks)))
+        theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+        got, cnt, st = run_gpu(ac, theta0, ups, pulls, 0.07, dev, chunks=chunks, history=d)
+        want = run_oracle(theta0, ups, pulls, 0.07)
+        assert st.t == Q
+        assert compare(got, want, f"{plan}/history trial {trial}, calls {chunks[:6]}...") == 0
+
+
+def test_one_update_per_call_is_the_server_loop_of_the_paper(ac, dev):
+    """Q = 1 per call: Alg. 2 literally.  Staleness up to the whole trace."""
+    rng = np.random.default_rng(32)
+    sizes, Q, d = [2500, 64], 120, 40
+    ups = random_updates(rng, sizes, Q, 0.1)
+    pulls = [int(rng.integers(max(0, q - d), q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.05, dev, chunks=[1] * Q, history=d)
+    want = run_oracle(theta0, ups, pulls, 0.05)
+    assert compare(got, want, "one update per call") == 0
+    # a pull older than the trace is refused and changes nothing
+    theta = [torch.from_numpy(t.copy()).to(dev) for t in theta0]
+    u = ac.Update.from_host(*ups[0], dev, pull_ts=Q - d - 1)
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_apply_workspace(sizes, [u], st)
+    assert e.value.code == -9
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_apply(theta, st, [u], 0.05, ws)
+    assert e.value.code == -9 and st.t == Q
+    u.pull_ts = Q - d                                    # the oldest remembered update: accepted
+    assert ac.adacomp_apply_workspace(sizes, [u], st) > 0
+
+
+def test_cnn_queue_in_calls_of_eight_with_history(ac, dev):
+    """cnn tensors, 48 updates (1%, chosen with torch.topk here), staleness uniform in [1, 48],
+    applied eight per call with a 48-deep trace."""
+    cfg = "cnn_apply"
+    Q, d = 48, 48
+    rng = np.random.default_rng(33)
+    stale = rng.integers(1, d + 1, Q).tolist()
+    pulls = workloads.pull_timestamps(stale)
+    ups = []
+    for q in range(Q):
+        off, idx, val = [0], [], []
+        for g in workloads.gradient(cfg, 300 + q, device=dev):
+            k = max(1, g.numel() // 100)
+            i = torch.topk(g.abs(), k).indices.sort().values
+            idx.append(i.cpu().numpy().astype(np.uint32))
+            val.append(g[i].cpu().numpy())
+            off.append(off[-1] + k)
+        ups.append((np.array(off, dtype=np.uint64), np.concatenate(idx), np.concatenate(val)))
+    theta0 = [t.numpy() for t in workloads.theta0(cfg)]
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.01, dev, chunks=[8] * 6, history=d)
+    want = run_oracle(theta0, ups, pulls, 0.01, method=oracle.HISTORY_BITMAP)
+    assert compare(got, want, "cnn queue, calls of 8, history 48") == 0
