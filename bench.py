@@ -3,8 +3,9 @@
 Workload ("flat", the roofline configuration): a stream of 1B-element fp32 gradients in
 100 tensors of 10M, mixture 95% N(0,1e-5) + 5% N(0,1e-2), rate 0.5% per tensor, 16
 queued worker updates with staleness uniform in [1,16].  One step = one pass of the
-whole path over one batch of 16 worker gradients, all resident in HBM: 16 x
-adacomp_select (one per gradient), then one adacomp_apply of the 16-update queue.
+whole path over one batch of 16 worker gradients, all resident in HBM: adacomp_select
+over all of them (one call over the 1600 tensors by default, or 16 calls with
+--per-gradient-calls), then one adacomp_apply of the 16-update queue.
 value = gradient elements compressed and applied per second = 16e9 / step time.
 
 Prints ONE JSON line.  `roofline` is for the dominant kernel (select's streaming filter
@@ -52,6 +53,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel in one extra untimed step")
+    ap.add_argument("--per-gradient-calls", action="store_true",
+                    help="one adacomp_select call per worker gradient instead of one call over all 16")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the 16 independent selects of a step are spread over (each has its own workspace)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -81,21 +84,37 @@ def main():
     state = ac.State(theta)
     cap = sum(ac.adacomp_count(n, rate) for n in sizes)
     updates = [ac.Update(L, cap, dev) for _ in range(Q)]
-    ns = max(1, args.streams)
+    batched = not args.per_gradient_calls
+    ns = 1 if batched else max(1, args.streams)
     streams = [torch.cuda.Stream(device=dev) for _ in range(ns)] if ns > 1 else [torch.cuda.current_stream(dev)]
     sel_bytes = ac.adacomp_select_workspace(sizes, rate)
     sel_wss = [torch.empty(sel_bytes, dtype=torch.uint8, device=dev) for _ in range(ns)]
     sel_ws = sel_wss[0]
     for q in range(Q):      # fills layer_off so that the apply workspace can be sized
         ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
+    if batched:
+        # the C ABI takes any list of tensors: all 16 worker gradients (1600 tensors) go through ONE
+        # select call, so the small per-call kernels are paid once; its output buffers are then
+        # viewed as the 16 worker updates (100 tensors each, own pull timestamp) that apply takes
+        all_tensors = [t for g in grads for t in g]
+        big = ac.Update(L * Q, cap * Q, dev)
+        sel_ws = None
+        sel_wss = [torch.empty(ac.adacomp_select_workspace(sizes * Q, rate), dtype=torch.uint8, device=dev)]
+        ac.adacomp_select(all_tensors, rate, big, sel_wss[0])
+        updates = [big.view(q * L, (q + 1) * L) for q in range(Q)]
     app_ws = torch.empty(ac.adacomp_apply_workspace(sizes, updates), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     main = torch.cuda.current_stream(dev)
 
     def selects():
-        # the 16 worker updates are independent: spread them over the streams, then join
         t0 = state.t
+        if batched:
+            for q in range(Q):
+                updates[q].pull_ts = t0 + pulls[q]
+            ac.adacomp_select(all_tensors, rate, big, sel_wss[0])
+            return
+        # the 16 worker updates are independent: spread them over the streams, then join
         if ns > 1:
             ready = main.record_event()
             for st in streams:
@@ -136,7 +155,9 @@ def main():
 
     f_ms, f_n = prof["filter"]
     f_avg_s = 1e-3 * f_ms / f_n
-    alg_bytes = 4.0 * N + 8.0 * cap           # per launch: every element read once, every selected pair written
+    per_launch = Q if batched else 1          # worker gradients one filter launch streams through
+    # per launch: every element read once, every selected pair written
+    alg_bytes = per_launch * (4.0 * N + 8.0 * cap)
     achieved = alg_bytes / f_avg_s / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "filter_flat_traffic.json")
@@ -150,8 +171,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "flat: 100 tensors x 10M fp32 = 1e9 elements per worker gradient, "
                                "95% N(0,1e-5) + 5% N(0,1e-2), rate 0.5% per tensor, 16 queued updates, "
-                               "staleness U[1,16]; step = 16 selects + 1 apply of the queue",
-                   "select_streams": ns,
+                               "staleness U[1,16]; step = select of the 16 worker gradients + 1 apply of the queue",
+                   "select_calls_per_step": 1 if batched else Q, "select_streams": ns,
                    "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q},
         "roofline": {"bound": "hbm", "kernel": "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -172,7 +193,7 @@ def main():
     torch.cuda.synchronize()
     if args.breakdown:
         kernels = {k: {"ms_total": round(v[0], 4), "launches": v[1]} for k, v in ac.adacomp_profile_stop().items()}
-    sel_ms, app_ms = ev[0].elapsed_time(ev[1]) / Q, ev[1].elapsed_time(ev[2])
+    sel_ms, app_ms = ev[0].elapsed_time(ev[1]) / Q, ev[1].elapsed_time(ev[2])   # select time per worker gradient
     out["select_ms_per_update"] = sel_ms
     out["apply_ms_per_queue"] = app_ms
     out["select_algorithmic_frac_of_peak"] = (4.0 * N + 8.0 * cap) / (sel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS

@@ -89,12 +89,14 @@ typedef struct {
 
 /* Parameter-server staleness state (Alg. 2; Sec. 4 "Algorithm details": the PS keeps a
  * timestamp and a trace of received updates).  Caller-owned memory whose contents the
- * library defines; zero-initialise t, history_len and cnt[][] for a fresh server.
+ * library defines; zero-initialise t and history_len for a fresh server.
  *   t            i: number of updates applied so far (advanced by adacomp_apply)
- *   cnt          HOST array [num_layers] of DEVICE pointers; cnt[l][k] (uint32, n_l of
- *                them) = number of applied updates whose entry for parameter k of tensor
- *                l was non-zero.  Inside one adacomp_apply call sigma_k of eq. 3 is a
- *                difference of two readings of it.
+ *   cnt          HOST array [num_layers] of DEVICE pointers; cnt[l] holds n_l uint32
+ *                counters, one per parameter of tensor l.  Scratch of the library: when a
+ *                call executes update by update, every applied non-zero entry for k
+ *                increments cnt[l][k], and the part of sigma_k (eq. 3) that lies inside
+ *                the call is a difference of two readings of it.  Only differences are
+ *                used: the values need no initialisation and mean nothing between calls.
  *   history_cap  d: how many applied updates the trace remembers (Sec. 4 "Complexity":
  *                the last d updates, d = the worst delay); 0 = none
  *   history_len  remembered so far (maintained by adacomp_apply)

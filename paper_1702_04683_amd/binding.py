@@ -115,6 +115,23 @@ class Update:
                        self.layer_off_dev.data_ptr(), self.idx.data_ptr(), self.val.data_ptr(),
                        self.cap, self.pull_ts)
 
+    def view(self, layer_lo, layer_hi, pull_ts=0):
+        """The tensors [layer_lo, layer_hi) of this update as an update of their own (shares the
+        idx/val storage).  Valid once adacomp_select has returned for this update: the host copy
+        of layer_off is filled by then, the device arrays follow in stream order."""
+        off = self.offsets
+        base = off[layer_lo]
+        rel = [o - base for o in off[layer_lo:layer_hi + 1]]
+        v = Update.__new__(Update)
+        v.num_layers = layer_hi - layer_lo
+        v.cap = rel[-1]
+        v.pull_ts = int(pull_ts)
+        v.layer_off = (C.c_uint64 * (v.num_layers + 1))(*rel)
+        v.layer_off_dev = torch.tensor(rel, dtype=torch.int64, device=self.idx.device)
+        v.idx = self.idx[base:base + max(v.cap, 1)]
+        v.val = self.val[base:base + max(v.cap, 1)]
+        return v
+
     @classmethod
     def from_host(cls, layer_off, idx, val, device, pull_ts=0):
         """Upload an update given as host arrays (what a PS would receive from the wire)."""

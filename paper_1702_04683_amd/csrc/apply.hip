@@ -1,29 +1,33 @@
 // adacomp_apply: loop body of Alg. 2 (eqs. 3, 4, 5) for a queue of sparse updates.
 //
-// Per-parameter staleness without searching a history: cnt[k] counts the applied
-// updates whose entry for parameter k was non-zero, so the sum of indicators of eq. 3
-// over u = j .. i-1 is cnt_k(at time i) - cnt_k(at time j).
+// Two execution plans for the part of the work inside one call, chosen on the host from
+// sizes alone:
 //
-// Two execution plans, chosen on the host from sizes alone:
-//
-//   scatter  one launch per update, in queue order.  The reading cnt_k(j) is taken by a
-//            gather ("snapshot") of cnt at the update's own indices, enqueued where PS
-//            time equals the update's pull timestamp.  Indices inside one update are
-//            unique, so the scatter needs no atomics.  Each random 4-byte access moves a
-//            whole cache line: right for short or very sparse queues.
+//   scatter  one launch per update, in queue order.  Per-parameter staleness without
+//            searching a history: cnt[k] is incremented by every applied non-zero entry for
+//            k, so the sum of indicators of eq. 3 over u = j .. i-1 is cnt_k(at time i) -
+//            cnt_k(at time j).  The reading cnt_k(j) is taken by a gather ("snapshot") of cnt
+//            at the update's own indices, enqueued where PS time equals the update's pull
+//            timestamp.  Only differences of cnt are used, so its starting values do not
+//            matter.  Indices inside one update are unique, so the scatter needs no atomics.
+//            Each random 4-byte access moves a whole cache line: right for short or very
+//            sparse queues.
 //
 //   sweep    one launch for the whole queue.  Parameters are independent of each other
 //            (the result for k depends only on the touches of k, in time order), so a
 //            workgroup owns a tile of consecutive coordinates, collects the slices of
 //            all Q sorted index lists that fall into its tile (slice bounds come from a
 //            bisection kernel), groups them by coordinate with a counting sort in LDS,
-//            and replays every coordinate's touches in time order in registers.  For a
-//            touch by update q pulled at j, sigma_k is the number of earlier non-zero
-//            touches of k by updates u with j <= u < q: eq. 3 evaluated on the tile's own
-//            lists.  Theta and cnt are read and written once per touched line instead of
-//            once per touch.  A tile whose lists do not fit LDS is replayed update by
-//            update from global memory by a second kernel (snapshot scheme, one
-//            workgroup per such tile).
+//            and replays every coordinate's touches in time order.  For a touch by update q
+//            pulled at j, sigma_k is the number of earlier non-zero touches of k by updates
+//            u with j <= u < q: eq. 3 evaluated on the tile's own lists; cnt is not needed.
+//            Theta is read and written once per touched coordinate instead of once per
+//            touch.  A tile whose lists do not fit LDS is replayed update by update from
+//            global memory by a second kernel (snapshot scheme on cnt, one workgroup per
+//            such tile).
+//
+// The part of an update's window that lies before the call is searched in the remembered
+// updates (k_history) and handed to either plan as a per-entry addend.
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
@@ -377,9 +381,9 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
     // per touch (dense over the lists, PER_THREAD touches per thread): its rank in time among
     // the touches of its coordinate, its staleness sigma (eq. 3 on the coordinate's own list),
     // and the product alpha_k * value (eq. 5 and the multiply of eq. 4), stored in time order.
-    // The earliest touch of a coordinate also fetches Theta_k and cnt_k and will fold the list.
+    // The earliest touch of a coordinate also fetches Theta_k and will fold the list.
     float theta[PER_THREAD];
-    uint32_t count[PER_THREAD], lo[PER_THREAD], hi[PER_THREAD], coord[PER_THREAD];
+    uint32_t lo[PER_THREAD], hi[PER_THREAD], coord[PER_THREAD];
 #pragma unroll
     for (uint32_t j = 0; j < PER_THREAD; ++j) {
         const uint32_t x = tid + j * BLOCK;
@@ -406,23 +410,17 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
             hi[j] = end;
             coord[j] = cx;
             theta[j] = pd.theta[c0 + cx];
-            count[j] = pd.cnt[c0 + cx];
         }
     }
     __syncthreads();
 
-    // per coordinate: subtract its products in time order (eq. 4), count its non-zero touches
+    // per coordinate: subtract its products in time order (eq. 4)
 #pragma unroll
     for (uint32_t j = 0; j < PER_THREAD; ++j) {
         if (hi[j] <= lo[j]) continue;
         float th = theta[j];
-        uint32_t nonzero_touches = 0;
-        for (uint32_t m = lo[j]; m < hi[j]; ++m) {
-            th = __fsub_rn(th, s_prod[m]);
-            nonzero_touches += s_key[m] >> 31;
-        }
+        for (uint32_t m = lo[j]; m < hi[j]; ++m) th = __fsub_rn(th, s_prod[m]);
         pd.theta[c0 + coord[j]] = th;
-        if (nonzero_touches) pd.cnt[c0 + coord[j]] = count[j] + nonzero_touches;
     }
 }
 
