@@ -222,10 +222,12 @@ def test_extreme_staleness_long_queue(ac, dev):
 
 
 def test_flat_config_full_size_sampled(ac, dev):
-    """The roofline configuration as bench.py runs it: 100 tensors of 10M parameters, 16 queued
-    0.5% updates (selected on the GPU from 16 seeded 1B-element gradients), staleness uniform
-    in [1, 16].  The oracle replays three whole tensors (its own selection, its own apply); on
-    every tensor exactly the parameters named by some update may have changed."""
+    """The roofline configuration in the launch shapes bench.py times: 16 seeded 1B-element worker
+    gradients (100 tensors of 10M each) go through ONE adacomp_select call over the 1600 tensors
+    at 0.5%; its output is viewed as 16 updates (staleness uniform in [1, 16]) and applied by one
+    adacomp_apply call to 100 tensors of 10M parameters.  The oracle replays sampled tensors
+    (its own selection from the same bits, its own apply); properties that hold at any size are
+    checked on many more."""
     cfg, rate = "flat", 0.005
     sizes = workloads.sizes_of(cfg)
     L, Q, lr = len(sizes), 16, workloads.CONFIGS[cfg]["lr"]
@@ -233,25 +235,36 @@ def test_flat_config_full_size_sampled(ac, dev):
     sample = [0, 41, 99]
     theta = workloads.theta0(cfg, device=dev)
     theta0 = {l: theta[l].cpu().numpy().copy() for l in sample}
-    ups, host_g = [], {l: [] for l in sample}
-    ws = None
-    for q in range(Q):
-        print(f"[apply] flat: select update {q}", flush=True)
-        g = workloads.gradient(cfg, q, device=dev)
-        for l in sample:
-            host_g[l].append(g[l].cpu().numpy())
-        if ws is None:
-            ws = torch.empty(ac.adacomp_select_workspace(sizes, rate), dtype=torch.uint8, device=dev)
-        ups.append(gpu_select(ac, g, rate, pull_ts=pulls[q], ws=ws))
-        del g
+    print("[apply] flat: generating 16 gradients (64 GB)", flush=True)
+    grads = [workloads.gradient(cfg, q, device=dev) for q in range(Q)]
+    host_g = {l: [grads[q][l].cpu().numpy() for q in range(Q)] for l in sample}
+    k = ac.adacomp_count(sizes[0], rate)
+    print("[apply] flat: one select call over 1600 tensors", flush=True)
+    big = gpu_select(ac, [t for g in grads for t in g], rate)
+    assert big.offsets == [k * i for i in range(L * Q + 1)]
+    # select, any size: per tensor the threshold is the k-th largest magnitude, everything above it is
+    # there, ties go to the lowest indices, values are the tensor's own bits (every 8th tensor)
+    for t in range(0, L * Q, 8):
+        g = grads[t // L][t % L]
+        idx = big.idx[t * k:(t + 1) * k].to(torch.int64)
+        val = big.val[t * k:(t + 1) * k]
+        assert bool((idx[1:] > idx[:-1]).all()) and 0 <= int(idx[0]) and int(idx[-1]) < sizes[t % L]
+        assert torch.equal(g[idx].view(torch.int32), val.view(torch.int32))
+        key = g.view(torch.int32) & 0x7FFFFFFF
+        T = int((val.view(torch.int32) & 0x7FFFFFFF).min())
+        n_gt = int((key > T).sum())
+        assert n_gt < k <= int((key >= T).sum()), f"tensor {t}: threshold"
+        assert int((key[idx] > T).sum()) == n_gt, f"tensor {t}: an entry above the threshold is missing"
+        assert torch.equal(idx[key[idx] == T], torch.nonzero(key == T).flatten()[:k - n_gt]), f"tensor {t}: ties"
+    del grads
+    ups = [big.view(q * L, (q + 1) * L, pull_ts=pulls[q]) for q in range(Q)]
     st = ac.State(theta)
-    aws = torch.empty(ac.adacomp_apply_workspace(sizes, ups), dtype=torch.uint8, device=dev)
+    aws = torch.empty(ac.adacomp_apply_workspace(sizes, ups, st), dtype=torch.uint8, device=dev)
     print("[apply] flat: gpu apply", flush=True)
     ac.adacomp_apply(theta, st, ups, lr, aws)
     torch.cuda.synchronize()
     assert st.t == Q
-    # on every tensor: parameters no update names are untouched, the others moved
-    k = ac.adacomp_count(sizes[0], rate)
+    # apply, any size: parameters no update names are untouched, the others moved
     theta_before = workloads.theta0(cfg, device=dev)
     for l in range(L):
         touched = torch.zeros(sizes[l], dtype=torch.bool, device=dev)
@@ -264,6 +277,9 @@ def test_flat_config_full_size_sampled(ac, dev):
     print("[apply] flat: oracle on sampled tensors", flush=True)
     for l in sample:
         o_ups = oracle_select_parallel([[x] for x in host_g[l]], rate, threads=8)
+        for q, (o, i, v) in enumerate(o_ups):       # the batched select against the oracle, entry by entry
+            assert np.array_equal(ups[q].idx[l * k:(l + 1) * k].cpu().numpy().view(np.uint32), i), (q, l)
+            assert np.array_equal(ups[q].val[l * k:(l + 1) * k].cpu().numpy().view(np.uint32), v.view(np.uint32))
         want = run_oracle([theta0[l]], o_ups, pulls, lr)
         assert compare([theta[l].cpu().numpy()], want, f"flat tensor {l}") == 0
 
