@@ -87,18 +87,19 @@ def main():
     batched = not args.per_gradient_calls
     ns = 1 if batched else max(1, args.streams)
     streams = [torch.cuda.Stream(device=dev) for _ in range(ns)] if ns > 1 else [torch.cuda.current_stream(dev)]
-    sel_bytes = ac.adacomp_select_workspace(sizes, rate)
-    sel_wss = [torch.empty(sel_bytes, dtype=torch.uint8, device=dev) for _ in range(ns)]
-    sel_ws = sel_wss[0]
-    for q in range(Q):      # fills layer_off so that the apply workspace can be sized
-        ac.adacomp_select(grads[q], rate, updates[q], sel_ws)
-    if batched:
+    sel_wss = []
+    if not batched:
+        sel_bytes = ac.adacomp_select_workspace(sizes, rate)
+        sel_wss = [torch.empty(sel_bytes, dtype=torch.uint8, device=dev) for _ in range(ns)]
+    if not batched:
+        for q in range(Q):      # fills layer_off so that the apply workspace can be sized
+            ac.adacomp_select(grads[q], rate, updates[q], sel_wss[q % ns])
+    else:
         # the C ABI takes any list of tensors: all 16 worker gradients (1600 tensors) go through ONE
         # select call, so the small per-call kernels are paid once; its output buffers are then
         # viewed as the 16 worker updates (100 tensors each, own pull timestamp) that apply takes
         all_tensors = [t for g in grads for t in g]
         big = ac.Update(L * Q, cap * Q, dev)
-        sel_ws = None
         sel_wss = [torch.empty(ac.adacomp_select_workspace(sizes * Q, rate), dtype=torch.uint8, device=dev)]
         ac.adacomp_select(all_tensors, rate, big, sel_wss[0])
         updates = [big.view(q * L, (q + 1) * L) for q in range(Q)]
@@ -161,9 +162,9 @@ def main():
     achieved = alg_bytes / f_avg_s / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "filter_flat_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath):   # HBM bytes per launch from the committed rocprofv3 --pmc summary
         with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+            traffic = json.load(f).get("hbm_bytes_per_launch_batched" if batched else "hbm_bytes_per_launch")
     out = {
         "metric": "gradient elements/sec compressed+applied",
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
