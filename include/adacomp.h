@@ -171,7 +171,7 @@ int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_state_t
  *   params   HOST [L]; data DEVICE, updated in place
  *   st       HOST struct; st->num_layers == L; st->cnt HOST [L] of DEVICE pointers
  *   updates  HOST [Q]; each must have num_layers == L, idx < n_l, strictly ascending
- *            per tensor (malformed index lists are undefined behaviour);
+ *            per tensor (see adacomp_update_validate for updates from elsewhere);
  *            pull_ts <= apply time of that update (else ADACOMP_ERR_FUTURE_PULL) and
  *            pull_ts >= st->t - (remembered updates) (else ADACOMP_ERR_HISTORY): an
  *            update pulled before this call has the earlier part of its window
@@ -187,6 +187,28 @@ int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_state_t
 int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, adacomp_state_t *st,
                   const adacomp_update_t *updates, uint32_t Q, float lr,
                   void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* The same queue with the learning-rate rule the paper ascribes to its competitors, ASGD and
+ * Comp-ASGD (Sec. 5.2: "the learning rate is divided by staleness and is global to each
+ * update"): sigma = i - j for every entry of an update, alpha = lr / sigma if sigma != 0.
+ * (Their selection, the largest entries across the whole model, is adacomp_select on the
+ * model passed as one tensor.)  Arguments, checks and stream semantics as adacomp_apply;
+ * no trace and no counters are needed: st->cnt and the history fields are neither read
+ * nor written, any pull_ts <= apply time is accepted.  workspace: DEVICE, 256-byte aligned,
+ * at least 32 * (L + 1) bytes rounded up to 256. */
+int adacomp_apply_global_staleness(const adacomp_param_layer_t *params, uint32_t L, adacomp_state_t *st,
+                                   const adacomp_update_t *updates, uint32_t Q, float lr,
+                                   void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Check an update that did not come from adacomp_select (adacomp_apply skips entries whose
+ * index is outside the tensor, but otherwise trusts its input: an index list that is not
+ * strictly ascending gives unspecified parameter values).  Enqueues one pass over the
+ * indices that leaves in *flags_dev (DEVICE uint32, read it after the stream has drained):
+ * 0 = well formed; bit 0: an index >= its tensor's size; bit 1: indices of a tensor not
+ * strictly ascending; bit 2: layer_off_dev[L] differs from the host layer_off[L].
+ *   n_dev  DEVICE [L] tensor sizes */
+int adacomp_update_validate(const adacomp_update_t *update, const uint64_t *n_dev, uint32_t L,
+                            uint32_t *flags_dev, void *hip_stream);
 
 /* Static, human-readable text for a return code. */
 const char *adacomp_strerror(int code);
@@ -214,6 +236,7 @@ enum {
     ADACOMP_KERNEL_BOUNDS,         /* apply: slice of every update per coordinate tile          */
     ADACOMP_KERNEL_SWEEP,          /* apply: eqs. 3-5 for the whole queue, tile by tile         */
     ADACOMP_KERNEL_SWEEP_SLOW,     /* apply: tiles whose touch lists exceed LDS                 */
+    ADACOMP_KERNEL_VALIDATE,       /* adacomp_update_validate                                   */
     ADACOMP_KERNEL_COUNT
 };
 

@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     adacomp_select,
     adacomp_apply_workspace,
     adacomp_apply,
+    adacomp_apply_global_staleness,
+    adacomp_update_validate,
     adacomp_strerror,
     adacomp_kernel_name,
     adacomp_profile_start,

@@ -68,6 +68,10 @@ def load_library():
     lib.adacomp_apply.restype = C.c_int
     lib.adacomp_apply.argtypes = [C.POINTER(_Layer), u32, C.POINTER(_State), C.POINTER(_Update), u32,
                                   C.c_float, vp, sz, vp]
+    lib.adacomp_apply_global_staleness.restype = C.c_int
+    lib.adacomp_apply_global_staleness.argtypes = lib.adacomp_apply.argtypes
+    lib.adacomp_update_validate.restype = C.c_int
+    lib.adacomp_update_validate.argtypes = [C.POINTER(_Update), vp, u32, vp, vp]
     lib.adacomp_strerror.restype = C.c_char_p
     lib.adacomp_strerror.argtypes = [C.c_int]
     lib.adacomp_profile_start.restype = C.c_int
@@ -244,7 +248,29 @@ def adacomp_apply(params, state, updates, lr, workspace, stream=None):
     return state
 
 
-KERNEL_COUNT = 20
+def adacomp_apply_global_staleness(params, state, updates, lr, workspace, stream=None):
+    """The competitors' rule (one learning rate per update, lr / global staleness).  Asynchronous."""
+    dev = workspace.device
+    arr = (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
+    rc = load_library().adacomp_apply_global_staleness(
+        _layers(params), len(params), C.byref(state._c), arr, len(updates), float(lr), workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream, dev))
+    if rc:
+        raise AdaCompError(rc, "adacomp_apply_global_staleness")
+    return state
+
+
+def adacomp_update_validate(update, sizes_dev, flags_dev, stream=None):
+    """Enqueue the well-formedness check of `update`; flags_dev (1 x int32 device tensor) holds the
+    result once the stream has drained.  sizes_dev: int64 device tensor of the tensor sizes."""
+    cu = update.c_struct()
+    rc = load_library().adacomp_update_validate(C.byref(cu), sizes_dev.data_ptr(), sizes_dev.numel(),
+                                                flags_dev.data_ptr(), _stream_ptr(stream, flags_dev.device))
+    if rc:
+        raise AdaCompError(rc, "adacomp_update_validate")
+
+
+KERNEL_COUNT = 21
 
 
 def adacomp_kernel_name(kernel_id):

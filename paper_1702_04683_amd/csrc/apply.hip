@@ -111,7 +111,8 @@ __global__ __launch_bounds__(BLOCK) void k_snapshot(const ParamDesc *P, uint32_t
     for (uint32_t i = 0; i < ITEMS; ++i, e += BLOCK) {
         if (e >= total) break;
         while (e >= off[l + 1]) ++l;
-        snap[e] = P[l].cnt[idx[e]];
+        const uint32_t k = idx[e];
+        if (k < P[l].n) snap[e] = P[l].cnt[k];  // an index outside the tensor (malformed update) is skipped
     }
 }
 
@@ -158,6 +159,7 @@ __global__ __launch_bounds__(BLOCK) void k_scatter_apply(const ParamDesc *P, uin
         if (e >= total) break;
         while (e >= off[l + 1]) ++l;
         const uint32_t k = idx[e];
+        if (k >= P[l].n) continue;  // malformed update: skipped, never dereferenced
         const float v = val[e];
         const bool nonzero = is_nonzero(v);
         float *theta = P[l].theta + k;
@@ -169,6 +171,39 @@ __global__ __launch_bounds__(BLOCK) void k_scatter_apply(const ParamDesc *P, uin
         *theta = step(*theta, lr, sigma, v);
         if (nonzero) *cnt = c + 1;
     }
+}
+
+// The rule the paper ascribes to its competitors (Sec. 5.2): one learning rate per update,
+// alpha divided by the update's global staleness i - j.
+__global__ __launch_bounds__(BLOCK) void k_scatter_apply_global(const ParamDesc *P, uint32_t L, const uint64_t *off,
+                                                                const uint32_t *idx, const float *val,
+                                                                uint64_t total, float lr, uint32_t sigma) {
+    uint64_t e = (uint64_t)blockIdx.x * (BLOCK * ITEMS) + threadIdx.x;
+    if (e >= total) return;
+    uint32_t l = layer_of(off, L, e);
+#pragma unroll
+    for (uint32_t i = 0; i < ITEMS; ++i, e += BLOCK) {
+        if (e >= total) break;
+        while (e >= off[l + 1]) ++l;
+        const uint32_t k = idx[e];
+        if (k >= P[l].n) continue;
+        float *theta = P[l].theta + k;
+        *theta = step(*theta, lr, sigma, val[e]);
+    }
+}
+
+// flags[0] |= 1 if an index is outside its tensor, |= 2 if the indices of a tensor are not
+// strictly ascending, |= 4 if the device copy of the offsets differs from the host's total.
+__global__ __launch_bounds__(BLOCK) void k_validate(const uint64_t *n, uint32_t L, const uint64_t *off,
+                                                    const uint32_t *idx, uint64_t total, uint32_t *flags) {
+    const uint64_t e = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (e == 0 && off[L] != total) atomicOr(flags, 4u);
+    if (e >= total || off[L] != total) return;
+    const uint32_t l = layer_of(off, L, e);
+    uint32_t bad = 0;
+    if (idx[e] >= n[l]) bad |= 1u;
+    if (e > off[l] && idx[e - 1] >= idx[e]) bad |= 2u;
+    if (bad) atomicOr(flags, bad);
 }
 
 // ------------------------------------------------------------------ sweep plan
@@ -236,7 +271,7 @@ __device__ __forceinline__ uint32_t load_slices(const Sweep &sw, uint32_t t, uin
         const uint32_t *row = sw.B + (uint64_t)q * (sw.ntiles + 1) + t;
         const UpdDesc u = sw.U[q];
         b0 = row[0];
-        len = row[1] - b0;
+        len = row[1] >= b0 ? row[1] - b0 : 0u;  // bounds of an unsorted (malformed) list may cross
         sl.idx[threadIdx.x] = u.idx;
         sl.val[threadIdx.x] = u.val;
         sl.pre[threadIdx.x] = u.pre;
@@ -435,7 +470,10 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
             for (uint32_t a = sw.pa_off[q]; a < sw.pa_off[q + 1]; ++a) {
                 const UpdDesc u = sw.U[sw.pa_list[a]];
                 const uint32_t *row = sw.B + (uint64_t)sw.pa_list[a] * (sw.ntiles + 1) + t;
-                for (uint32_t e = row[0] + threadIdx.x; e < row[1]; e += BLOCK) u.snap[e] = pd.cnt[u.idx[e]];
+                for (uint32_t e = row[0] + threadIdx.x; e < row[1]; e += BLOCK) {
+                    const uint32_t k = u.idx[e];
+                    if (k < pd.n) u.snap[e] = pd.cnt[k];
+                }
             }
             __syncthreads();
             const UpdDesc u = sw.U[q];
@@ -443,6 +481,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
             const bool stale = q - u.pull >= (u.pre ? 1u : 2u);  // has a snapshot (host: same rule)
             for (uint32_t e = row[0] + threadIdx.x; e < row[1]; e += BLOCK) {
                 const uint32_t k = u.idx[e];
+                if (k >= pd.n) continue;
                 const float v = u.val[e];
                 const uint32_t c = pd.cnt[k];
                 const uint32_t sigma = (stale ? c - u.snap[e] : 0u) + (u.pre ? u.pre[e] : 0u);
@@ -753,5 +792,72 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         st->history_len = (uint32_t)(len < st->history_cap ? len : st->history_cap);
     }
     st->t = t0 + Q;
+    return ADACOMP_OK;
+}
+
+extern "C" int adacomp_apply_global_staleness(const adacomp_param_layer_t *params, uint32_t L, adacomp_state_t *st,
+                                              const adacomp_update_t *updates, uint32_t Q, float lr,
+                                              void *workspace, size_t ws_bytes, void *hip_stream) {
+    if (!st || (L && !params)) return ADACOMP_ERR_NULL;
+    if (st->num_layers != L) return ADACOMP_ERR_LAYER_MISMATCH;
+    if (!std::isfinite(lr)) return ADACOMP_ERR_LR;
+    int rc = check_updates(L, updates, Q);
+    if (rc) return rc;
+    std::vector<ParamDesc> table((size_t)L + 1, ParamDesc{nullptr, nullptr, 0, 0});
+    for (uint32_t l = 0; l < L; ++l) {
+        if (params[l].n > 0xffffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
+        if (params[l].n && !params[l].data) return ADACOMP_ERR_NULL;
+        if ((uintptr_t)params[l].data & 3u) return ADACOMP_ERR_ALIGNMENT;
+        table[l] = ParamDesc{params[l].data, nullptr, params[l].n, 0};
+    }
+    const uint64_t t0 = st->t;
+    for (uint32_t q = 0; q < Q; ++q) {
+        const adacomp_update_t &u = updates[q];
+        const uint64_t total = u.layer_off[L];
+        for (uint32_t l = 0; l < L; ++l)
+            if (u.layer_off[l + 1] - u.layer_off[l] > params[l].n) return ADACOMP_ERR_LAYER_MISMATCH;
+        if (total > u.cap) return ADACOMP_ERR_CAPACITY;
+        if (total && (!u.idx || !u.val || !u.layer_off_dev)) return ADACOMP_ERR_NULL;
+        if (((uintptr_t)u.idx & 3u) || ((uintptr_t)u.val & 3u) || ((uintptr_t)u.layer_off_dev & 7u))
+            return ADACOMP_ERR_ALIGNMENT;
+        if (u.pull_ts > t0 + q) return ADACOMP_ERR_FUTURE_PULL;
+        if (t0 + q - u.pull_ts > 0xffffffffull) return ADACOMP_ERR_HISTORY;
+    }
+    const size_t need = align_up(((size_t)L + 1) * sizeof(ParamDesc), 256);
+    if (!workspace || ((uintptr_t)workspace & 255u) || ws_bytes < need) return ADACOMP_ERR_WORKSPACE;
+    if (Q == 0) return ADACOMP_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    ParamDesc *P = static_cast<ParamDesc *>(workspace);
+    if (put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess) return ADACOMP_ERR_HIP;
+    for (uint32_t q = 0; q < Q; ++q) {
+        const adacomp_update_t &u = updates[q];
+        const uint64_t total = u.layer_off[L];
+        if (total == 0) continue;
+        const dim3 grid((unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS)));
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, k_scatter_apply_global, grid, dim3(BLOCK), s, P, L,
+                       u.layer_off_dev, u.idx, u.val, total, lr, (uint32_t)(t0 + q - u.pull_ts));
+        CHECK_LAUNCH();
+    }
+    st->t = t0 + Q;
+    return ADACOMP_OK;
+}
+
+extern "C" int adacomp_update_validate(const adacomp_update_t *update, const uint64_t *n_dev, uint32_t L,
+                                       uint32_t *flags_dev, void *hip_stream) {
+    if (!update || !flags_dev || (L && !n_dev)) return ADACOMP_ERR_NULL;
+    int rc = check_updates(L, update, 1);
+    if (rc) return rc;
+    const uint64_t total = update->layer_off[L];
+    if (total > update->cap) return ADACOMP_ERR_CAPACITY;
+    if (!update->layer_off_dev || (total && !update->idx)) return ADACOMP_ERR_NULL;
+    if (((uintptr_t)update->idx & 3u) || ((uintptr_t)update->layer_off_dev & 7u) || ((uintptr_t)n_dev & 7u) ||
+        ((uintptr_t)flags_dev & 3u))
+        return ADACOMP_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (fill_u32_async(flags_dev, 0u, 1, s) != hipSuccess) return ADACOMP_ERR_HIP;
+    const dim3 grid((unsigned)((total + BLOCK) / BLOCK));
+    ADACOMP_LAUNCH(ADACOMP_KERNEL_VALIDATE, k_validate, grid, dim3(BLOCK), s, n_dev, L, update->layer_off_dev,
+                   update->idx, total, flags_dev);
+    CHECK_LAUNCH();
     return ADACOMP_OK;
 }

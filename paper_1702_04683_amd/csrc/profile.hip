@@ -99,6 +99,7 @@ extern "C" const char *adacomp_kernel_name(int id) {
         case ADACOMP_KERNEL_BOUNDS: return "bounds";
         case ADACOMP_KERNEL_SWEEP: return "sweep";
         case ADACOMP_KERNEL_SWEEP_SLOW: return "sweep_slow";
+        case ADACOMP_KERNEL_VALIDATE: return "validate";
         default: return "?";
     }
 }

@@ -422,3 +422,81 @@ def test_cnn_queue_in_calls_of_eight_with_history(ac, dev):
     got, _, st = run_gpu(ac, theta0, ups, pulls, 0.01, dev, chunks=[8] * 6, history=d)
     want = run_oracle(theta0, ups, pulls, 0.01, method=oracle.HISTORY_BITMAP)
     assert compare(got, want, "cnn queue, calls of 8, history 48") == 0
+
+
+def test_global_staleness_rule_of_the_competitors(ac, dev):
+    """adacomp_apply_global_staleness against the oracle's GLOBAL mode (Sec. 5.2: one learning rate
+    per update, divided by its global staleness), and the hand-worked chronology, where the
+    per-parameter and the global rule differ."""
+    mk = lambda d: (np.array([0, len(d)], dtype=np.uint64), np.array(sorted(d), dtype=np.uint32),
+                    np.array([d[k] for k in sorted(d)], dtype=np.float32))
+    ups = [mk({0: 1, 1: 1}), mk({1: 1, 2: 1}), mk({1: 1, 2: 1, 3: 1})]
+
+    def run_global(theta_host, updates_host, pulls, lr):
+        theta = [torch.from_numpy(t.copy()).to(dev) for t in theta_host]
+        us = [ac.Update.from_host(o, i, v, dev, pull_ts=p) for (o, i, v), p in zip(updates_host, pulls)]
+        st = ac.State(theta)
+        ws = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+        ac.adacomp_apply_global_staleness(theta, st, us, lr, ws)
+        torch.cuda.synchronize()
+        assert st.t == len(us)
+        return [t.cpu().numpy() for t in theta]
+
+    got = run_global([np.zeros(4, np.float32)], ups, [0, 0, 0], 1.0)
+    assert got[0].tolist() == [-1.0, -2.5, -1.5, -0.5]            # tests/golden/apply_chronology.json
+    rng = np.random.default_rng(51)
+    sizes = [5000, 3, 0, 777]
+    Q = 30
+    ups = random_updates(rng, sizes, Q, 0.2, zero_frac=0.1)
+    pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    got = run_global(theta0, ups, pulls, 0.05)
+    want = [t.copy() for t in theta0]
+    ps = oracle.ParameterServer(want)
+    for (o, i, v), p in zip(ups, pulls):
+        ps.apply(o, i, v, p, 0.05, mode=oracle.GLOBAL)
+    assert compare(got, want, "global staleness") == 0
+    per_param = run_oracle(theta0, ups, pulls, 0.05)
+    assert any(not np.array_equal(a, b) for a, b in zip(want, per_param)), "the two rules must differ here"
+
+
+def test_update_validate_and_malformed_entries_are_skipped(ac, dev, monkeypatch):
+    rng = np.random.default_rng(52)
+    sizes = [3000, 40]
+    sizes_dev = torch.tensor(sizes, dtype=torch.int64, device=dev)
+    flags = torch.zeros(1, dtype=torch.int32, device=dev)
+    good = random_updates(rng, sizes, 1, 0.1)[0]
+
+    def check(o, i, v):
+        u = ac.Update.from_host(o, i, v, dev)
+        ac.adacomp_update_validate(u, sizes_dev, flags)
+        torch.cuda.synchronize()
+        return int(flags.item())
+
+    assert check(*good) == 0
+    o, i, v = good
+    bad = i.copy(); bad[5] = 3000                    # outside tensor 0
+    assert check(o, bad, v) & 1
+    bad = i.copy(); bad[7], bad[8] = i[8], i[7]      # not ascending
+    assert check(o, bad, v) == 2
+    bad = i.copy(); bad[8] = bad[7]                  # duplicate
+    assert check(o, bad, v) == 2
+    bad = i.copy(); bad[int(o[1])] = 40              # outside tensor 1
+    assert check(o, bad, v) & 1
+    # apply skips an out-of-range entry and treats all others as the oracle does
+    Q = 6
+    ups = random_updates(rng, sizes, Q, 0.1)
+    pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    broken = [(o.copy(), i.copy(), v.copy()) for o, i, v in ups]
+    oo, ii, vv = broken[3]
+    last = int(oo[1]) - 1                             # last entry of tensor 0 of update 3
+    ii[last] = 3000 + 17
+    cleaned = list(ups)
+    keep = np.ones(ups[3][1].size, dtype=bool); keep[last] = False
+    cleaned[3] = (np.array([0, int(oo[1]) - 1, int(oo[2]) - 1], dtype=np.uint64), ups[3][1][keep], ups[3][2][keep])
+    want = run_oracle(theta0, cleaned, pulls, 0.05)
+    for plan in ("scatter", "sweep"):
+        monkeypatch.setenv("ADACOMP_APPLY_PLAN", plan)
+        got, _, _ = run_gpu(ac, theta0, broken, pulls, 0.05, dev)
+        assert compare(got, want, f"{plan}: out-of-range entry skipped") == 0

@@ -189,3 +189,17 @@ def test_flat_config_full_size(ac, dev):
         assert int((sel_key > T).sum()) == n_gt, f"tensor {l}: an entry above the threshold is missing"
         eq_all = torch.nonzero(key == T).flatten()[:k - n_gt]
         assert torch.equal(idx[sel_key == T], eq_all), f"tensor {l}: tie rule"
+
+
+def test_whole_model_selection_is_select_on_one_tensor(ac, dev):
+    """The competitors' selection (Sec. 4 'Selection method': the largest entries across the whole
+    model) is the same call on the model passed as a single tensor; it differs from the per-tensor rule."""
+    g = workloads.gradient("cnn_select", 3, device=dev)
+    flat = torch.cat([x.view(-1) for x in g])
+    u = check(ac, [flat], 0.01, what="whole model")
+    per = gpu_select(ac, g, 0.01)
+    base = np.cumsum([0] + [x.numel() for x in g])
+    per_global = np.concatenate([per.idx[per.offsets[l]:per.offsets[l + 1]].cpu().numpy().view(np.uint32).astype(np.int64) + base[l]
+                                 for l in range(len(g))])
+    whole = u.idx[:u.total].cpu().numpy().view(np.uint32).astype(np.int64)
+    assert whole.size != per_global.size or not np.array_equal(whole, per_global)
