@@ -7,6 +7,7 @@ arguments.  PyTorch is used to own device memory and streams.
 from .binding import (  # noqa: F401
     AdaCompError,
     Update,
+    Layers,
     State,
     adacomp_count,
     adacomp_select_workspace,

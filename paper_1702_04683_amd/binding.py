@@ -105,6 +105,12 @@ class Update:
         self.layer_off_dev = torch.zeros(self.num_layers + 1, dtype=torch.int64, device=device)
         self.idx = torch.empty(max(self.cap, 1), dtype=torch.int32, device=device)   # uint32 bit patterns
         self.val = torch.empty(max(self.cap, 1), dtype=torch.float32, device=device)
+        self._bind()
+
+    def _bind(self):
+        # addresses are fixed for the life of the object: fetched once, not on every call
+        self._ptrs = (C.cast(self.layer_off, C.POINTER(C.c_uint64)), self.layer_off_dev.data_ptr(),
+                      self.idx.data_ptr(), self.val.data_ptr())
 
     @property
     def offsets(self):
@@ -115,9 +121,7 @@ class Update:
         return int(self.layer_off[self.num_layers])
 
     def c_struct(self):
-        return _Update(self.num_layers, C.cast(self.layer_off, C.POINTER(C.c_uint64)),
-                       self.layer_off_dev.data_ptr(), self.idx.data_ptr(), self.val.data_ptr(),
-                       self.cap, self.pull_ts)
+        return _Update(self.num_layers, *self._ptrs, self.cap, self.pull_ts)
 
     def view(self, layer_lo, layer_hi, pull_ts=0):
         """The tensors [layer_lo, layer_hi) of this update as an update of their own (shares the
@@ -134,6 +138,7 @@ class Update:
         v.layer_off_dev = torch.tensor(rel, dtype=torch.int64, device=self.idx.device)
         v.idx = self.idx[base:base + max(v.cap, 1)]
         v.val = self.val[base:base + max(v.cap, 1)]
+        v._bind()
         return v
 
     @classmethod
@@ -199,7 +204,21 @@ def adacomp_select_workspace(sizes, rate, k_override=None):
     return int(out.value)
 
 
+class Layers:
+    """A list of tensors marshalled once (adacomp_layer_t array); pass it wherever a list of
+    tensors is taken when the same tensors go through many calls.  Keeps the tensors alive."""
+
+    def __init__(self, tensors):
+        self.tensors = list(tensors)
+        self._arr = _layers(self.tensors)
+
+    def __len__(self):
+        return len(self.tensors)
+
+
 def _layers(tensors):
+    if isinstance(tensors, Layers):
+        return tensors._arr
     arr = (_Layer * max(len(tensors), 1))()
     for l, t in enumerate(tensors):
         if t.dtype != torch.float32 or not t.is_contiguous():

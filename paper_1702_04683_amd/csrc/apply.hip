@@ -42,11 +42,12 @@ namespace {
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t WAVES = BLOCK / WAVE;
 constexpr uint32_t ITEMS = 4;          // scatter plan: entries per thread
-constexpr uint32_t TILE_MAX = 2048;    // sweep plan: coordinates per tile (power of two, >= BLOCK)
+constexpr uint32_t TILE_MAX = 2048;    // sweep plan: most coordinates per tile (power of two); dense queues get smaller tiles
 constexpr uint32_t STAGE_CAP = 512;    // sweep plan: entries of the whole queue a tile can hold in LDS
-constexpr uint32_t LIST_MAX = 128;     // sweep plan: touches of one coordinate the fast kernel replays
 constexpr uint32_t SLOW_GRID = 1024;
 constexpr uint32_t PASS = 256;           // sweep plan: updates whose slices are staged together
+// one launch costs about as much as this many bytes of memory traffic (4 us at 5 TB/s)
+constexpr double LAUNCH_COST_BYTES = 20e6;
 static_assert((TILE_MAX & (TILE_MAX - 1)) == 0 && TILE_MAX >= BLOCK && STAGE_CAP % BLOCK == 0 && STAGE_CAP <= 65535,
               "tile and stage sizes");
 
@@ -320,7 +321,10 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
     const uint32_t tile = 1u << sw.tile_shift;
     const ParamDesc pd = sw.P[sw.tile_tensor[t]];
     const uint32_t c0 = (t - (uint32_t)pd.tile_base) << sw.tile_shift;
-    const uint32_t per_thread = tile / BLOCK;
+    // the scan over the tile's coordinates: per_thread consecutive ones per thread; a tile
+    // smaller than the workgroup leaves the upper threads without any
+    const uint32_t per_thread = tile >= BLOCK ? tile / BLOCK : 1u;
+    const bool scans = tid * per_thread < tile;
 
     const uint32_t ncoord = pd.n - c0 < tile ? (uint32_t)(pd.n - c0) : tile;
 
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
         for (uint32_t j = 0; j < PER_THREAD; ++j) {
             if (tid + j * BLOCK >= n_pass) continue;
             if (c[j] >= ncoord) s_bad = 1;  // only a malformed (unsorted) index list gets here
-            else if (atomicAdd(&s_cur[slot(c[j])], 1u) >= LIST_MAX) s_bad = 1;
+            else atomicAdd(&s_cur[slot(c[j])], 1u);
         }
         __syncthreads();
     }
@@ -372,14 +376,16 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
     // counts -> list starts (exclusive scan, per_thread consecutive coordinates per thread)
     {
         uint32_t sum = 0;
-        for (uint32_t j = 0; j < per_thread; ++j) sum += s_cur[slot(tid * per_thread + j)];
+        if (scans)
+            for (uint32_t j = 0; j < per_thread; ++j) sum += s_cur[slot(tid * per_thread + j)];
         uint32_t all;
         uint32_t run = block_exclusive_scan<WAVES>(sum, s_wave, all);
-        for (uint32_t j = 0; j < per_thread; ++j) {
-            const uint32_t n_touch = s_cur[slot(tid * per_thread + j)];
-            s_cur[slot(tid * per_thread + j)] = run;
-            run += n_touch;
-        }
+        if (scans)
+            for (uint32_t j = 0; j < per_thread; ++j) {
+                const uint32_t n_touch = s_cur[slot(tid * per_thread + j)];
+                s_cur[slot(tid * per_thread + j)] = run;
+                run += n_touch;
+            }
         __syncthreads();
     }
 
@@ -537,7 +543,8 @@ int check_pulls(const adacomp_state_t *st, const adacomp_update_t *updates, uint
 }
 
 // Plan and workspace layout from sizes and timestamps alone.  The sweep pays 16 bytes per
-// parameter plus about 30 per entry; the scatter about 440 bytes per entry (measured line traffic).
+// parameter plus about 30 per entry and three launches; the scatter about 440 bytes per entry
+// (measured line traffic) and one or two launches per update.
 void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_update_t *updates, uint32_t Q,
                  Layout &lay) {
     double entries = 0, params = 0;
@@ -555,15 +562,28 @@ void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_updat
     const bool never = force && std::strcmp(force, "scatter") == 0;
     const bool always = force && std::strcmp(force, "sweep") == 0;
     if (!never && Q >= 2 && Q <= 0x7fffu && fits32 && L > 0 && params > 0 && entries > 0) {
-        // tile: about STAGE_CAP / 2 queued entries per tile on average
+        // tile: about STAGE_CAP / 2 queued entries per tile on average, as long as the table of
+        // slice bounds (Q x tiles) stays below twice the size of the updates themselves
         const double per_coord = entries / params;
+        auto tiles_at = [&](uint32_t sh) {
+            uint64_t t = 0;
+            for (uint32_t l = 0; l < L; ++l) t += (n[l] + (1ull << sh) - 1) >> sh;
+            return t;
+        };
         uint32_t shift = 0;
         while ((2u << shift) <= TILE_MAX) ++shift;  // log2(TILE_MAX)
-        while ((1u << shift) > BLOCK && (double)(1u << shift) * per_coord > STAGE_CAP / 2) --shift;
-        uint64_t ntiles = 0;
-        for (uint32_t l = 0; l < L; ++l) ntiles += (n[l] + (1ull << shift) - 1) >> shift;
-        const double sweep_cost = 1.25 * (16.0 * params + 30.0 * entries + 8.0 * (double)Q * (double)ntiles);
-        if (ntiles < 0x7fffffffull && (always || 440.0 * entries > sweep_cost)) {
+        const double table_budget = std::max(64.0 * 1048576.0, 16.0 * entries);
+        while (shift > 0 && (double)(1u << shift) * per_coord > STAGE_CAP / 2 &&
+               4.0 * (double)Q * (double)tiles_at(shift - 1) <= table_budget)
+            --shift;
+        const uint64_t ntiles = tiles_at(shift);
+        uint32_t launches = 0;  // of the scatter plan
+        for (uint32_t q = 0; q < Q; ++q)
+            if (updates[q].layer_off[L] > 0) launches += (t0 + q - updates[q].pull_ts >= 2) ? 2u : 1u;
+        const double sweep_cost = 1.25 * (16.0 * params + 30.0 * entries + 8.0 * (double)Q * (double)ntiles) +
+                                  3.0 * LAUNCH_COST_BYTES;
+        const double scatter_cost = 440.0 * entries + LAUNCH_COST_BYTES * launches;
+        if (ntiles < 0x7fffffffull && (always || scatter_cost > sweep_cost)) {
             lay.sweep = true;
             lay.tile_shift = shift;
             lay.ntiles = ntiles;

@@ -298,7 +298,7 @@ def test_both_plans_on_the_same_queues(ac, dev, plan, monkeypatch):
     # dense: every update touches 60% of every tensor -> tiles overflow the stage
     sizes = [5_000, 777]
     cases.append(("dense", sizes, random_updates(rng, sizes, 30, 0.6)))
-    # hot coordinates: 400 updates all hitting the same few parameters -> lists beyond LIST_MAX
+    # hot coordinates: 400 updates all hitting the same few parameters -> lists longer than a tile can stage
     sizes = [10_000, 3]
     hot = []
     for q in range(400):

@@ -1,5 +1,5 @@
 """Seeded synthetic inputs for the AdaComp hot path: gradients, initial parameters
-and staleness draws shaped like the five benchmark configurations.
+and staleness draws shaped like the benchmark configurations.
 
 This module holds NO arithmetic of the method (no selection, no staleness or
 learning-rate formula).  It is the only code that the CPU oracle's tests and the
@@ -18,6 +18,9 @@ SIZES = {
     "mid": [34848, 307200, 884736, 663552, 442368, 37748736, 16777216, 40960],
     # 1B-element stream, 100 tensors of 10M
     "flat": [10_000_000] * 100,
+    # a two-conv, two-FC MNIST network with the parameter count of Sec. 5.1 (211,690): conv 3x3x1x32 + b,
+    # conv 3x3x32x32 + b, FC 1568x128 + b, FC 128x10 + b (the text gives the total only; these shapes sum to it)
+    "paper_cnn": [288, 32, 9216, 32, 200704, 128, 1280, 10],
 }
 
 CONFIGS = {
@@ -28,6 +31,9 @@ CONFIGS = {
                 lr=0.01, seed=3000),
     "flat": dict(sizes="flat", dist="mixture", rates=[0.005], Q=16, max_staleness=16,
                  lr=0.01, seed=4000),
+    # the network size and worker count of Sec. 5.1 with the compression ratios of Sec. 5.3 and 5.4
+    "paper_cnn": dict(sizes="paper_cnn", dist="heavy_tail", rates=[0.1, 0.01, 0.001, 0.0001], Q=200,
+                      max_staleness=200, lr=0.01, seed=6000),
     "adversarial": dict(sizes="adversarial", dist="adversarial", rates=[0.0, None, 1.0],
                         lr=0.01, seed=5000),
 }
