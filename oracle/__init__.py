@@ -52,6 +52,12 @@ def _load():
         lib.adacomp_oracle_ps_timestamp.argtypes = [vp]
         lib.adacomp_oracle_ps_apply.restype = C.c_int
         lib.adacomp_oracle_ps_apply.argtypes = [vp, vp, vp, vp, vp, vp, u64, f64, C.c_int, vp]
+        lib.adacomp_oracle_wire_bound.restype = u64
+        lib.adacomp_oracle_wire_bound.argtypes = [vp, u32]
+        lib.adacomp_oracle_wire_pack.restype = u64
+        lib.adacomp_oracle_wire_pack.argtypes = [vp, vp, vp, u32, vp, u64]
+        lib.adacomp_oracle_wire_unpack.restype = C.c_int
+        lib.adacomp_oracle_wire_unpack.argtypes = [vp, u64, u32, u64, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -149,3 +155,35 @@ class ParameterServer:
             self.close()
         except Exception:
             pass
+
+
+def wire_bound(layer_off):
+    off = np.ascontiguousarray(layer_off, dtype=np.uint64)
+    return int(_load().adacomp_oracle_wire_bound(_ptr(off), off.size - 1))
+
+
+def wire_pack(layer_off, idx, val):
+    """The update as the words of the wire format (numpy uint32)."""
+    off = np.ascontiguousarray(layer_off, dtype=np.uint64)
+    idx = np.ascontiguousarray(idx, dtype=np.uint32)
+    val = np.ascontiguousarray(val, dtype=np.float32)
+    out = np.empty(wire_bound(off), dtype=np.uint32)
+    n = int(_load().adacomp_oracle_wire_pack(_ptr(off), _ptr(idx), _ptr(val), off.size - 1, _ptr(out), out.size))
+    if n == 0:
+        raise ValueError("indices of a tensor do not ascend strictly")
+    return out[:n].copy()
+
+
+def wire_unpack(words, L, cap=None):
+    """(layer_off, idx, val) of a packed update; raises ValueError on a malformed stream."""
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    if cap is None:
+        cap = int(words.size)
+    off = np.zeros(L + 1, dtype=np.uint64)
+    idx = np.zeros(max(cap, 1), dtype=np.uint32)
+    val = np.zeros(max(cap, 1), dtype=np.float32)
+    rc = int(_load().adacomp_oracle_wire_unpack(_ptr(words), words.size, L, cap, _ptr(off), _ptr(idx), _ptr(val)))
+    if rc:
+        raise ValueError(f"malformed wire stream (code {rc})")
+    total = int(off[L])
+    return off, idx[:total].copy(), val[:total].copy()

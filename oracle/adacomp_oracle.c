@@ -27,6 +27,12 @@
  *   "!= 0" in eq. 3   is_nonzero()        value != +-0 (denormals count)
  *   op order eq. 4-5  step_f32/step_f64   divide, multiply, subtract, each rounded
  *
+ * A third part is not from the paper, which leaves the byte encoding of an update
+ * open (footnote of Sec. 4 "Overview"): the wire format of this library (block-wise
+ * delta coding of the sorted indices, values as they are), written out from its
+ * definition in include/adacomp.h so that real bytes per update can be set against
+ * the paper's traffic model (Sec. 3.2: I x M x c).  Pins: tests/test_oracle_wire.py.
+ *
  * Parity pins: tests/test_oracle_select.py, tests/test_oracle_apply.py (closed
  * forms, brute force, library cross-checks, hand examples in tests/golden/).
  * The count rule and the "!= 0" reading are choices the paper does not
@@ -285,5 +291,137 @@ int adacomp_oracle_ps_apply(oracle_ps_t *ps, float *const *theta32, double *cons
     }
     if (history_append(ps, layer_off, idx, val)) return -1;
     ps->t = i + 1;
+    return 0;
+}
+
+
+/* ------------------------------------------------------------------ wire format
+ *
+ * Not from the paper (it leaves the encoding open).  Little-endian 32-bit words:
+ *
+ *   [0] magic 0x31434441   [1] L   [2],[3] total entries (low, high)
+ *   [4 .. 4+L)             k_l, entries of tensor l
+ *   first[B]               B = sum_l ceil(k_l / 64) blocks; a block is up to 64 consecutive
+ *                          entries of one tensor; first[b] = index of its first entry
+ *   width[B]               one byte per block, zero-padded to a whole word
+ *   deltas                 block after block: for the entries i = 1 .. m-1 of the block
+ *                          d_i = idx_i - idx_{i-1} - 1 (indices ascend strictly), each in
+ *                          w = width[b] bits, d_1 first, least significant bit first, bit p
+ *                          of the block's stream = bit (p mod 32) of its word p / 32; the
+ *                          last word is zero-padded; w = bit length of the largest d_i
+ *   values[total]          the fp32 bit patterns, in entry order
+ */
+
+#define WIRE_MAGIC 0x31434441u
+#define WIRE_BLOCK 64u
+
+static uint32_t bit_length(uint32_t x) {
+    uint32_t n = 0;
+    while (x) {
+        ++n;
+        x >>= 1;
+    }
+    return n;
+}
+
+/* Upper bound of the words adacomp_oracle_wire_pack can produce (every width 32). */
+uint64_t adacomp_oracle_wire_bound(const uint64_t *layer_off, uint32_t L) {
+    uint64_t blocks = 0, delta_words = 0;
+    for (uint32_t l = 0; l < L; ++l) {
+        const uint64_t k = layer_off[l + 1] - layer_off[l];
+        blocks += (k + WIRE_BLOCK - 1) / WIRE_BLOCK;
+        delta_words += k; /* at most one word per entry */
+    }
+    return 4 + (uint64_t)L + blocks + (blocks + 3) / 4 + delta_words + layer_off[L];
+}
+
+/* Returns the number of words written, or 0 if `cap` words do not suffice / the
+ * indices of a tensor do not ascend strictly. */
+uint64_t adacomp_oracle_wire_pack(const uint64_t *layer_off, const uint32_t *idx, const float *val,
+                                  uint32_t L, uint32_t *out, uint64_t cap) {
+    const uint64_t total = layer_off[L];
+    uint64_t blocks = 0;
+    for (uint32_t l = 0; l < L; ++l) blocks += (layer_off[l + 1] - layer_off[l] + WIRE_BLOCK - 1) / WIRE_BLOCK;
+    const uint64_t first_at = 4 + (uint64_t)L;
+    const uint64_t width_at = first_at + blocks;
+    const uint64_t delta_at = width_at + (blocks + 3) / 4;
+    if (delta_at > cap) return 0;
+    out[0] = WIRE_MAGIC;
+    out[1] = L;
+    out[2] = (uint32_t)(total & 0xffffffffu);
+    out[3] = (uint32_t)(total >> 32);
+    for (uint32_t l = 0; l < L; ++l) out[4 + l] = (uint32_t)(layer_off[l + 1] - layer_off[l]);
+    for (uint64_t w = width_at; w < delta_at; ++w) out[w] = 0;
+    uint64_t b = 0, pos = delta_at;
+    for (uint32_t l = 0; l < L; ++l) {
+        for (uint64_t e0 = layer_off[l]; e0 < layer_off[l + 1]; e0 += WIRE_BLOCK, ++b) {
+            const uint64_t e1 = e0 + WIRE_BLOCK < layer_off[l + 1] ? e0 + WIRE_BLOCK : layer_off[l + 1];
+            uint32_t largest = 0;
+            for (uint64_t e = e0 + 1; e < e1; ++e) {
+                if (idx[e] <= idx[e - 1]) return 0;
+                const uint32_t d = idx[e] - idx[e - 1] - 1;
+                if (d > largest) largest = d;
+            }
+            const uint32_t w = bit_length(largest);
+            out[first_at + b] = idx[e0];
+            out[width_at + b / 4] |= w << (8 * (b % 4));
+            const uint64_t bits = (e1 - e0 - 1) * w, words = (bits + 31) / 32;
+            if (pos + words > cap) return 0;
+            for (uint64_t x = 0; x < words; ++x) out[pos + x] = 0;
+            uint64_t p = 0; /* bit position in the block's stream */
+            for (uint64_t e = e0 + 1; e < e1; ++e) {
+                const uint32_t d = idx[e] - idx[e - 1] - 1;
+                for (uint32_t i = 0; i < w; ++i, ++p)
+                    if ((d >> i) & 1u) out[pos + p / 32] |= 1u << (p % 32);
+            }
+            pos += words;
+        }
+    }
+    if (pos + total > cap) return 0;
+    for (uint64_t e = 0; e < total; ++e) out[pos + e] = f32_bits(val[e]);
+    return pos + total;
+}
+
+/* Inverse.  layer_off (L+1), idx and val (cap entries) are outputs.  Returns 0, or a
+ * negative number naming what is wrong with the stream. */
+int adacomp_oracle_wire_unpack(const uint32_t *in, uint64_t nwords, uint32_t L, uint64_t cap,
+                               uint64_t *layer_off, uint32_t *idx, float *val) {
+    if (nwords < 4 || in[0] != WIRE_MAGIC) return -1;
+    if (in[1] != L || nwords < 4 + (uint64_t)L) return -2;
+    const uint64_t total = (uint64_t)in[2] | ((uint64_t)in[3] << 32);
+    uint64_t blocks = 0, sum = 0;
+    layer_off[0] = 0;
+    for (uint32_t l = 0; l < L; ++l) {
+        sum += in[4 + l];
+        layer_off[l + 1] = sum;
+        blocks += ((uint64_t)in[4 + l] + WIRE_BLOCK - 1) / WIRE_BLOCK;
+    }
+    if (sum != total || total > cap) return -3;
+    const uint64_t first_at = 4 + (uint64_t)L;
+    const uint64_t width_at = first_at + blocks;
+    const uint64_t delta_at = width_at + (blocks + 3) / 4;
+    if (delta_at > nwords) return -4;
+    uint64_t b = 0, pos = delta_at;
+    for (uint32_t l = 0; l < L; ++l) {
+        for (uint64_t e0 = layer_off[l]; e0 < layer_off[l + 1]; e0 += WIRE_BLOCK, ++b) {
+            const uint64_t e1 = e0 + WIRE_BLOCK < layer_off[l + 1] ? e0 + WIRE_BLOCK : layer_off[l + 1];
+            const uint32_t w = (in[width_at + b / 4] >> (8 * (b % 4))) & 0xffu;
+            if (w > 32) return -5;
+            const uint64_t words = ((e1 - e0 - 1) * w + 31) / 32;
+            if (pos + words > nwords) return -4;
+            uint64_t prev = in[first_at + b], p = 0;
+            idx[e0] = (uint32_t)prev;
+            for (uint64_t e = e0 + 1; e < e1; ++e) {
+                uint64_t d = 0;
+                for (uint32_t i = 0; i < w; ++i, ++p) d |= (uint64_t)((in[pos + p / 32] >> (p % 32)) & 1u) << i;
+                prev += d + 1;
+                if (prev > 0xffffffffull) return -6;
+                idx[e] = (uint32_t)prev;
+            }
+            pos += words;
+        }
+    }
+    if (pos + total != nwords) return -7;
+    memcpy(val, in + pos, total * sizeof(float));
     return 0;
 }
