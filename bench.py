@@ -57,6 +57,8 @@ def main():
                     help="one adacomp_select call per worker gradient instead of one call over all 16")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the 16 independent selects of a step are spread over (each has its own workspace)")
+    ap.add_argument("--wire", action="store_true",
+                    help="also encode / decode one worker update in the wire format and report bytes and times")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 4 GB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -201,6 +203,39 @@ def main():
     out["apply_entries_per_s"] = Q * cap / (app_ms * 1e-3)
     if kernels:
         out["kernels"] = kernels
+
+    if args.wire:      # one worker update (100 tensors x 50,000 entries) through the wire format and back
+        u = updates[0]
+        off = u.offsets
+        wire = torch.empty(ac.adacomp_wire_bound(off), dtype=torch.int32, device=dev)
+        nwords = torch.zeros(1, dtype=torch.int64, device=dev)
+        wws = torch.empty(max(256, ac.adacomp_wire_workspace(off)), dtype=torch.uint8, device=dev)
+        back = ac.Update(L, cap, dev)
+        for l in range(L + 1):
+            back.layer_off[l] = off[l]
+        flags = torch.zeros(1, dtype=torch.int32, device=dev)
+        ac.adacomp_wire_pack(u, wire, nwords, wws)
+        words = int(nwords.item())
+        reps = 20
+        tm = []
+        for fn in (lambda: ac.adacomp_wire_pack(u, wire, nwords, wws),
+                   lambda: ac.adacomp_wire_unpack(wire, words, back, flags, wws)):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            tm.append(1e3 * e0.elapsed_time(e1) / reps)
+        assert int(flags.item()) == 0 and torch.equal(back.idx[:cap], u.idx[:cap]) and \
+            torch.equal(back.val[:cap].view(torch.int32), u.val[:cap].view(torch.int32))
+        out["wire"] = {"entries": cap, "stream_bytes": 4 * words, "bytes_per_entry": 4.0 * words / cap,
+                       "raw_pairs_bytes": 8 * cap, "paper_model_bytes": 4 * cap,
+                       "pack_us": tm[0], "unpack_us": tm[1],
+                       "pack_GBps": (8.0 * cap + 4.0 * words) / (tm[0] * 1e-6) / 1e9,
+                       "unpack_GBps": (8.0 * cap + 4.0 * words) / (tm[1] * 1e-6) / 1e9}
 
     if not args.no_cpu_baseline:
         del grads

@@ -210,6 +210,48 @@ int adacomp_apply_global_staleness(const adacomp_param_layer_t *params, uint32_t
 int adacomp_update_validate(const adacomp_update_t *update, const uint64_t *n_dev, uint32_t L,
                             uint32_t *flags_dev, void *hip_stream);
 
+/* ---- wire format (not an operation of the paper) -----------------------------------
+ * The paper leaves the byte encoding of an update open (footnote of Sec. 4 "Overview")
+ * and models traffic as I x M x c (Sec. 3.2), values only.  These two calls turn an
+ * update into the stream of little-endian 32-bit words this library would send, and back,
+ * so that real bytes per update can be stated.  A block is up to 64 consecutive entries of
+ * one tensor; B = sum_l ceil(k_l / 64).
+ *
+ *   [0] magic 0x31434441  [1] L  [2],[3] total entries (low, high word)
+ *   [4 .. 4+L)            k_l
+ *   first[B]              index of the first entry of every block
+ *   width[B]              one byte per block, zero-padded to a whole word
+ *   deltas                block after block: for entries i = 1 .. m-1 of the block
+ *                         d_i = idx_i - idx_(i-1) - 1 in width[b] bits each, d_1 first,
+ *                         least significant bit first, bit p of the block's stream = bit
+ *                         (p mod 32) of its word p / 32, last word zero-padded;
+ *                         width[b] = bit length of the block's largest d_i (0 .. 32)
+ *   values[total]         fp32 bit patterns in entry order
+ *
+ * adacomp_wire_bound: *words = the most words a stream for these HOST offsets can take.
+ * adacomp_wire_workspace: *bytes of DEVICE workspace either call needs (256-byte aligned). */
+int adacomp_wire_bound(const uint64_t *layer_off, uint32_t L, uint64_t *words);
+int adacomp_wire_workspace(const uint64_t *layer_off, uint32_t L, size_t *bytes);
+
+/* Encode `update` (as adacomp_select leaves it; totals above 2^32 - 1 entries are refused
+ * with ADACOMP_ERR_LAYER_TOO_LARGE) into wire[0 .. wire_cap) (DEVICE, 4-byte aligned).
+ * *wire_words_dev (DEVICE uint64, 8-byte aligned) receives the length of the stream; if it
+ * exceeds wire_cap the stream is incomplete (nothing is written beyond wire_cap), so size the
+ * buffer with adacomp_wire_bound.  Asynchronous on hip_stream; allocates nothing. */
+int adacomp_wire_pack(const adacomp_update_t *update, uint32_t *wire, uint64_t wire_cap,
+                      uint64_t *wire_words_dev, void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Decode wire[0 .. wire_words) (DEVICE) into `update`.  The receiver knows what it expects:
+ * update->num_layers and the HOST update->layer_off (k_l follows from (n_l, c) alone, Alg. 1)
+ * must be filled in by the caller; idx, val (cap >= total) and layer_off_dev are written.
+ * The stream is not trusted: no read goes beyond wire_words and no write beyond the expected
+ * counts, and *flags_dev (DEVICE uint32, valid once the stream has drained) reports
+ * 0 = decoded; bit 0: header differs from what was expected; bit 1: a width above 32;
+ * bit 2: stream length inconsistent with its widths; bit 3: an index beyond 2^32 - 1.
+ * With a flag set the output arrays hold unspecified values. */
+int adacomp_wire_unpack(const uint32_t *wire, uint64_t wire_words, const adacomp_update_t *update,
+                        uint32_t *flags_dev, void *workspace, size_t ws_bytes, void *hip_stream);
+
 /* Static, human-readable text for a return code. */
 const char *adacomp_strerror(int code);
 
@@ -237,6 +279,10 @@ enum {
     ADACOMP_KERNEL_SWEEP,          /* apply: eqs. 3-5 for the whole queue, tile by tile         */
     ADACOMP_KERNEL_SWEEP_SLOW,     /* apply: tiles whose touch lists exceed LDS                 */
     ADACOMP_KERNEL_VALIDATE,       /* adacomp_update_validate                                   */
+    ADACOMP_KERNEL_WIRE_MEASURE,   /* wire: width and word count of every 64-entry block        */
+    ADACOMP_KERNEL_WIRE_SCAN,      /* wire: word offsets of the blocks, header                  */
+    ADACOMP_KERNEL_WIRE_WRITE,     /* wire: packed index gaps and values out                    */
+    ADACOMP_KERNEL_WIRE_READ,      /* wire: indices and values back                             */
     ADACOMP_KERNEL_COUNT
 };
 

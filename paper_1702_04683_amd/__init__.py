@@ -16,6 +16,10 @@ from .binding import (  # noqa: F401
     adacomp_apply,
     adacomp_apply_global_staleness,
     adacomp_update_validate,
+    adacomp_wire_bound,
+    adacomp_wire_workspace,
+    adacomp_wire_pack,
+    adacomp_wire_unpack,
     adacomp_strerror,
     adacomp_kernel_name,
     adacomp_profile_start,

@@ -72,6 +72,14 @@ def load_library():
     lib.adacomp_apply_global_staleness.argtypes = lib.adacomp_apply.argtypes
     lib.adacomp_update_validate.restype = C.c_int
     lib.adacomp_update_validate.argtypes = [C.POINTER(_Update), vp, u32, vp, vp]
+    lib.adacomp_wire_bound.restype = C.c_int
+    lib.adacomp_wire_bound.argtypes = [C.POINTER(u64), u32, C.POINTER(u64)]
+    lib.adacomp_wire_workspace.restype = C.c_int
+    lib.adacomp_wire_workspace.argtypes = [C.POINTER(u64), u32, C.POINTER(sz)]
+    lib.adacomp_wire_pack.restype = C.c_int
+    lib.adacomp_wire_pack.argtypes = [C.POINTER(_Update), vp, u64, vp, vp, sz, vp]
+    lib.adacomp_wire_unpack.restype = C.c_int
+    lib.adacomp_wire_unpack.argtypes = [vp, u64, C.POINTER(_Update), vp, vp, sz, vp]
     lib.adacomp_strerror.restype = C.c_char_p
     lib.adacomp_strerror.argtypes = [C.c_int]
     lib.adacomp_profile_start.restype = C.c_int
@@ -289,7 +297,46 @@ def adacomp_update_validate(update, sizes_dev, flags_dev, stream=None):
         raise AdaCompError(rc, "adacomp_update_validate")
 
 
-KERNEL_COUNT = 21
+def adacomp_wire_bound(layer_off):
+    """Most 32-bit words the wire stream of an update with these offsets can take."""
+    out = C.c_uint64(0)
+    rc = load_library().adacomp_wire_bound(_u64_array(layer_off), len(layer_off) - 1, C.byref(out))
+    if rc:
+        raise AdaCompError(rc, "adacomp_wire_bound")
+    return int(out.value)
+
+
+def adacomp_wire_workspace(layer_off):
+    out = C.c_size_t(0)
+    rc = load_library().adacomp_wire_workspace(_u64_array(layer_off), len(layer_off) - 1, C.byref(out))
+    if rc:
+        raise AdaCompError(rc, "adacomp_wire_workspace")
+    return int(out.value)
+
+
+def adacomp_wire_pack(update, wire, wire_words_dev, workspace, stream=None):
+    """Encode `update` into `wire` (int32 device tensor); wire_words_dev (1 x int64 device tensor)
+    receives the stream length in words.  Asynchronous."""
+    cu = update.c_struct()
+    rc = load_library().adacomp_wire_pack(C.byref(cu), wire.data_ptr(), wire.numel(), wire_words_dev.data_ptr(),
+                                          workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                          _stream_ptr(stream, wire.device))
+    if rc:
+        raise AdaCompError(rc, "adacomp_wire_pack")
+
+
+def adacomp_wire_unpack(wire, wire_words, update, flags_dev, workspace, stream=None):
+    """Decode the first `wire_words` words of `wire` into `update`, whose host layer_off holds the
+    expected offsets.  flags_dev: 1 x int32 device tensor, 0 once decoded cleanly.  Asynchronous."""
+    cu = update.c_struct()
+    rc = load_library().adacomp_wire_unpack(wire.data_ptr(), int(wire_words), C.byref(cu), flags_dev.data_ptr(),
+                                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                            _stream_ptr(stream, wire.device))
+    if rc:
+        raise AdaCompError(rc, "adacomp_wire_unpack")
+
+
+KERNEL_COUNT = 25
 
 
 def adacomp_kernel_name(kernel_id):

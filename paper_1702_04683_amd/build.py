@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadacomp.so")
-SOURCES = ["select.hip", "apply.hip", "profile.hip"]
+SOURCES = ["select.hip", "apply.hip", "wire.hip", "profile.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -100,6 +100,10 @@ extern "C" const char *adacomp_kernel_name(int id) {
         case ADACOMP_KERNEL_SWEEP: return "sweep";
         case ADACOMP_KERNEL_SWEEP_SLOW: return "sweep_slow";
         case ADACOMP_KERNEL_VALIDATE: return "validate";
+        case ADACOMP_KERNEL_WIRE_MEASURE: return "wire_measure";
+        case ADACOMP_KERNEL_WIRE_SCAN: return "wire_scan";
+        case ADACOMP_KERNEL_WIRE_WRITE: return "wire_write";
+        case ADACOMP_KERNEL_WIRE_READ: return "wire_read";
         default: return "?";
     }
 }

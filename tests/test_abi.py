@@ -140,3 +140,20 @@ def test_apply_argument_checks_run_before_any_launch(lib):
     upd[0].pull_ts = 6
     assert call() == -7
     assert lib.adacomp_apply_workspace(n, 1, None, upd, 1, C.byref(need)) == -7
+
+
+def test_wire_host_side_checks(lib):
+    off = [0, 130, 130, 131]
+    B = 3 + 0 + 1
+    assert ac.adacomp_wire_bound(off) == 4 + 3 + B + 1 + 131 + 131
+    assert ac.adacomp_wire_bound(off) >= oracle.wire_bound(off)
+    assert ac.adacomp_wire_workspace(off) % 256 == 0
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_wire_bound([0, 5, 3])
+    assert e.value.code == -6
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_wire_bound([1, 5])
+    assert e.value.code == -6
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_wire_bound([0, 1 << 33])
+    assert e.value.code == -3
