@@ -283,6 +283,7 @@ enum {
     ADACOMP_KERNEL_WIRE_SCAN,      /* wire: word offsets of the blocks, header                  */
     ADACOMP_KERNEL_WIRE_WRITE,     /* wire: packed index gaps and values out                    */
     ADACOMP_KERNEL_WIRE_READ,      /* wire: indices and values back                             */
+    ADACOMP_KERNEL_SMALL,          /* select: a small tensor start to end in one workgroup      */
     ADACOMP_KERNEL_COUNT
 };
 

@@ -336,7 +336,7 @@ def adacomp_wire_unpack(wire, wire_words, update, flags_dev, workspace, stream=N
         raise AdaCompError(rc, "adacomp_wire_unpack")
 
 
-KERNEL_COUNT = 25
+KERNEL_COUNT = 26
 
 
 def adacomp_kernel_name(kernel_id):

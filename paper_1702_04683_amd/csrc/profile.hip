@@ -104,6 +104,7 @@ extern "C" const char *adacomp_kernel_name(int id) {
         case ADACOMP_KERNEL_WIRE_SCAN: return "wire_scan";
         case ADACOMP_KERNEL_WIRE_WRITE: return "wire_write";
         case ADACOMP_KERNEL_WIRE_READ: return "wire_read";
+        case ADACOMP_KERNEL_SMALL: return "small";
         default: return "?";
     }
 }

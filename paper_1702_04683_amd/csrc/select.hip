@@ -26,7 +26,14 @@
 //                         (index, value) pairs.
 // Tensors with k == n are copied (identity), tensors with k == 0 produce nothing,
 // tensors with k > n/8 skip steps 1-5.
+//
+// Small tensors (the whole CNN of Sec. 5.1 has 211,690 parameters) would pay about twenty
+// launches for microseconds of work: when the small tensors of a call fit the last-level
+// cache, each is selected by one workgroup in a single launch (k_small: the same 12 + 12 + 7
+// bit descent with LDS histograms, then the ordered write), and the pipeline above runs for
+// the large tensors only.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <cmath>
 #include <vector>
@@ -47,8 +54,19 @@ constexpr uint32_t SPIECES = 64;    // sampled pieces per sample-histogram workg
 constexpr uint32_t BLOCK = 256;     // threads per workgroup = 4 waves
 constexpr uint32_t WAVES = BLOCK / WAVE;
 constexpr uint32_t IDENT_TILE = BLOCK * 16;  // elements per identity-copy workgroup
+constexpr uint32_t SMALL_MAX = 1u << 18;     // largest tensor that one workgroup selects on its own
+constexpr uint64_t SMALL_TOTAL = 1ull << 26; // ... as long as all such tensors of the call hold no more elements than this
+constexpr uint32_t SBLOCK = 1024;            // threads of that workgroup
+constexpr uint32_t SWAVES = SBLOCK / WAVE;
 
-enum : uint32_t { MODE_EMPTY = 0, MODE_IDENTITY = 1, MODE_FILTER = 2, MODE_DENSE = 3 };
+enum : uint32_t { MODE_EMPTY = 0, MODE_IDENTITY = 1, MODE_FILTER = 2, MODE_DENSE = 3, MODE_SMALL = 4 };
+
+struct SmallDesc {  // a tensor selected by one workgroup
+    const float *g;
+    uint64_t out_off;
+    uint32_t n, k;
+};
+static_assert(sizeof(SmallDesc) % 8 == 0, "descriptor table is uploaded as 64-bit words");
 
 struct LayerDesc {
     const float *g;
@@ -95,11 +113,13 @@ struct Workspace {
     uint2 *cand;          // [cand_total] per-segment regions of (index, value bits)
     uint32_t *pack_idx;   // [cand_total] the same candidates packed per tensor
     uint32_t *pack_val;
+    SmallDesc *small;     // [nsmall]
     size_t bytes;
 };
 
 struct Plan {
     std::vector<LayerDesc> desc;  // L+1, the last one carries the totals
+    std::vector<SmallDesc> small; // tensors left to k_small, largest first
     uint64_t nseg_total = 0, cand_total = 0, out_total = 0;
 };
 
@@ -114,6 +134,13 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
     if (!(rate >= 0.0 && rate <= 1.0)) return ADACOMP_ERR_RATE;
     plan.desc.assign((size_t)L + 1, LayerDesc{});
     uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, iblk = 0, gblk = 0;
+    // one workgroup per small tensor, if together they stay cache-sized (ADACOMP_SELECT_SMALL=0:
+    // never, for tests of the pipeline on small tensors)
+    uint64_t small_elems = 0;
+    for (uint32_t l = 0; l < L; ++l)
+        if (n[l] <= SMALL_MAX) small_elems += n[l];
+    const char *env = std::getenv("ADACOMP_SELECT_SMALL");
+    const bool small_ok = small_elems <= SMALL_TOTAL && !(env && env[0] == '0');
     for (uint32_t l = 0; l < L; ++l) {
         if (n[l] > 0xffffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
         uint64_t k64 = k_override ? k_override[l] : adacomp_count(n[l], rate);
@@ -137,6 +164,9 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
         } else if (d.k == d.n) {
             d.mode = MODE_IDENTITY;
             iblk += (n[l] + IDENT_TILE - 1) / IDENT_TILE;
+        } else if (small_ok && d.n <= SMALL_MAX) {
+            d.mode = MODE_SMALL;
+            plan.small.push_back(SmallDesc{d.g, out, d.n, d.k});
         } else {
             d.nseg = (uint32_t)((n[l] + WSEG - 1) / WSEG);
             d.mode = (8ull * d.k > d.n) ? MODE_DENSE : MODE_FILTER;
@@ -194,6 +224,8 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
     plan.nseg_total = seg;
     plan.cand_total = cand;
     plan.out_total = out;
+    std::stable_sort(plan.small.begin(), plan.small.end(),
+                     [](const SmallDesc &a, const SmallDesc &b) { return a.n > b.n; });
     return ADACOMP_OK;
 }
 
@@ -215,6 +247,7 @@ void carve(const Plan &plan, uint32_t L, void *base, Workspace &ws) {
     ws.cand = (uint2 *)take(plan.cand_total * sizeof(uint2));
     ws.pack_idx = (uint32_t *)take(plan.cand_total * sizeof(uint32_t));
     ws.pack_val = (uint32_t *)take(plan.cand_total * sizeof(uint32_t));
+    ws.small = (SmallDesc *)take(plan.small.size() * sizeof(SmallDesc));
     ws.bytes = off;
 }
 
@@ -624,6 +657,277 @@ __global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L) {
     }
 }
 
+// ---- small tensors: the whole selection of one tensor in one workgroup -------------
+// s_res[0] = the largest bin b with #{entries in bins >= b} >= want, s_res[1] = #{entries in
+// bins > b}.  The histogram holds at least `want` entries.  SBLOCK threads, nbins <= BINS.
+__device__ __forceinline__ void small_find_bin(const uint32_t *s_hist, uint32_t nbins, uint32_t want,
+                                               uint32_t *s_wave, uint32_t *s_res) {
+    const uint32_t per = nbins >= SBLOCK ? nbins / SBLOCK : 1u;  // bins per thread, taken from the top
+    const uint32_t first = threadIdx.x * per;
+    uint32_t sum = 0;
+    if (first < nbins)
+        for (uint32_t j = 0; j < per; ++j) sum += s_hist[nbins - 1 - (first + j)];
+    uint32_t all;
+    uint32_t run = block_exclusive_scan<SWAVES>(sum, s_wave, all);  // entries above this thread's bins
+    if (first < nbins && run < want && run + sum >= want) {       // exactly one thread
+        for (uint32_t j = 0; j < per; ++j) {
+            const uint32_t b = nbins - 1 - (first + j);
+            const uint32_t c = s_hist[b];
+            if (run + c >= want) {
+                s_res[0] = b;
+                s_res[1] = run;
+                break;
+            }
+            run += c;
+        }
+    }
+    __syncthreads();
+}
+
+constexpr uint32_t SCAND = 448;  // candidate slots per wave of k_small (16 waves: 56 KB of LDS)
+
+// Digit of `key` at a level of the descent, if the bits above the digit equal `prefix`.
+__device__ __forceinline__ bool small_digit(uint32_t key, uint32_t prefix, uint32_t pshift, uint32_t shift,
+                                            uint32_t nbins, uint32_t &digit) {
+    digit = (key >> shift) & (nbins - 1);
+    return (key >> pshift) == prefix;
+}
+
+// The quads q0 + u * stride (u < U) of a tensor; quads at or beyond q_end read as zeros.  A
+// single workgroup has few waves to hide memory latency with, so the aligned full quads are
+// fetched by U unconditional loads that are all in flight together (addresses past the range
+// are clamped and the result dropped); only a ragged last quad or an unaligned tensor takes
+// the conditional element-wise path.
+template <uint32_t U>
+__device__ __forceinline__ void small_load(const SmallDesc &d, bool vec, uint32_t q0, uint32_t stride,
+                                           uint32_t q_end, uint4 (&v)[U]) {
+    const uint32_t nfull = vec ? d.n / 4 : 0u;  // quads that one aligned 16-byte load can fetch
+    if (nfull) {
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t q = q0 + u * stride;
+            v[u] = load4_full<false>(d.g, (q < nfull ? q : nfull - 1) * 4);
+        }
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < U; ++u) {
+        const uint32_t q = q0 + u * stride;
+        if (q >= nfull) v[u] = q < q_end ? load4(d.g, q * 4, d.n, vec) : make_uint4(0, 0, 0, 0);
+    }
+}
+
+// Histogram of one level over the whole tensor.
+__device__ __forceinline__ void small_hist_global(const SmallDesc &d, bool vec, uint32_t *s_hist, uint32_t prefix,
+                                                  uint32_t pshift, uint32_t shift, uint32_t nbins) {
+    constexpr uint32_t U = 8;
+    const uint32_t nquads = (d.n + 3) / 4;
+    uint32_t zeros = 0;  // digit 0 (all exact zeros at the first level) is counted in a register
+    for (uint32_t q0 = threadIdx.x; q0 < nquads; q0 += U * SBLOCK) {
+        uint4 v[U];
+        small_load<U>(d, vec, q0, SBLOCK, nquads, v);
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t q = q0 + u * SBLOCK;
+            const uint32_t bits[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (uint32_t c = 0; c < 4; ++c) {
+                uint32_t digit;
+                if (q < nquads && q * 4 + c < d.n && small_digit(mag_key(bits[c]), prefix, pshift, shift, nbins, digit)) {
+                    if (digit == 0) ++zeros;
+                    else atomicAdd(&s_hist[digit], 1u);
+                }
+            }
+        }
+    }
+    if (zeros) atomicAdd(&s_hist[0], zeros);
+}
+
+// One workgroup selects one tensor: level-0 histogram over the tensor; then, in a second and
+// last read, every wave compacts the entries of its contiguous share that lie in the threshold
+// bin or above, in index order, into LDS; the two lower levels of the descent and the ordered
+// write work on those.  If the candidates do not fit LDS, the lower levels and the write read
+// the tensor again instead.
+__global__ __launch_bounds__(SBLOCK) void k_small(const SmallDesc *S, uint32_t *out_idx, uint32_t *out_val) {
+    __shared__ uint32_t s_hist[BINS];
+    __shared__ uint32_t s_cidx[SWAVES][SCAND];
+    __shared__ uint32_t s_cval[SWAVES][SCAND];
+    __shared__ uint32_t s_wave[SWAVES];
+    __shared__ uint32_t s_cnt[SWAVES], s_gt[SWAVES], s_eq[SWAVES];
+    __shared__ uint32_t s_res[2];
+    __shared__ uint32_t s_fail;
+    const SmallDesc d = S[blockIdx.x];
+    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wv = tid / WAVE;
+    const bool vec = ((uintptr_t)d.g & 15u) == 0;
+    const uint32_t nquads = (d.n + 3) / 4;
+
+    // level 0: bits 30..19 of the key
+    for (uint32_t i = tid; i < BINS; i += SBLOCK) s_hist[i] = 0;
+    if (tid == 0) s_fail = 0;
+    __syncthreads();
+    small_hist_global(d, vec, s_hist, 0u, 31u, 19u, BINS);
+    __syncthreads();
+    small_find_bin(s_hist, BINS, d.k, s_wave, s_res);
+    const uint32_t bin0 = s_res[0];
+    uint32_t prefix = bin0, k_rem = d.k - s_res[1];
+    const uint32_t ncand = s_res[1] + s_hist[bin0];  // entries in the threshold bin or above
+    __syncthreads();
+
+    bool in_lds = ncand <= SWAVES * SCAND;
+    if (in_lds) {
+        // ordered compaction of the candidates, wave by wave over contiguous shares
+        const uint32_t share = (nquads + SWAVES - 1) / SWAVES;
+        const uint32_t q_lo = wv * share, q_hi = q_lo + share < nquads ? q_lo + share : nquads;
+        uint32_t filled = 0;
+        bool ok = true;
+        constexpr uint32_t U = 8;
+        for (uint32_t p = q_lo; p < q_hi && ok; p += U * WAVE) {
+            uint4 v[U];
+            small_load<U>(d, vec, p + lane, WAVE, q_hi, v);
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                const uint32_t q = p + u * WAVE + lane;
+                const uint32_t bits[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+                bool take[4];
+                uint32_t before = 0, total = 0;  // candidates in lower lanes; in the whole piece
+#pragma unroll
+                for (uint32_t c = 0; c < 4; ++c) {
+                    take[c] = q < q_hi && q * 4 + c < d.n && (mag_key(bits[c]) >> 19) >= bin0;
+                    const uint64_t m = __ballot(take[c]);
+                    before += lanes_below(m);
+                    total += popc64(m);
+                }
+                if (filled + total > SCAND) {  // wave-uniform
+                    ok = false;
+                    break;
+                }
+                uint32_t at = filled + before;
+#pragma unroll
+                for (uint32_t c = 0; c < 4; ++c) {
+                    if (take[c]) {
+                        s_cidx[wv][at] = q * 4 + c;
+                        s_cval[wv][at] = bits[c];
+                        ++at;
+                    }
+                }
+                filled += total;
+            }
+        }
+        if (lane == 0) {
+            s_cnt[wv] = filled;
+            if (!ok) s_fail = 1;
+        }
+        __syncthreads();
+        in_lds = s_fail == 0;
+    }
+
+    // levels 1 and 2: bits 18..7 and 6..0, among the entries that share the prefix found so far
+#pragma unroll 1
+    for (int level = 1; level < 3; ++level) {
+        const uint32_t shift = level == 1 ? 7u : 0u;
+        const uint32_t nbins = level == 1 ? BINS : 128u;
+        const uint32_t pshift = level == 1 ? 19u : 7u;
+        for (uint32_t i = tid; i < nbins; i += SBLOCK) s_hist[i] = 0;
+        __syncthreads();
+        if (in_lds) {
+            uint32_t zeros = 0;
+            for (uint32_t e = lane; e < s_cnt[wv]; e += WAVE) {
+                uint32_t digit;
+                if (small_digit(mag_key(s_cval[wv][e]), prefix, pshift, shift, nbins, digit)) {
+                    if (digit == 0) ++zeros;
+                    else atomicAdd(&s_hist[digit], 1u);
+                }
+            }
+            if (zeros) atomicAdd(&s_hist[0], zeros);
+        } else {
+            small_hist_global(d, vec, s_hist, prefix, pshift, shift, nbins);
+        }
+        __syncthreads();
+        small_find_bin(s_hist, nbins, k_rem, s_wave, s_res);
+        prefix = (prefix << (level == 1 ? 12 : 7)) | s_res[0];
+        k_rem -= s_res[1];
+        __syncthreads();
+    }
+    const uint32_t T = prefix, r = k_rem;  // threshold key; entries equal to it to keep (lowest indices)
+
+    if (in_lds) {
+        // ordered write from the candidates: counts per wave, then every wave places its own
+        uint32_t n_gt = 0, n_eq = 0;
+        for (uint32_t e0 = 0; e0 < s_cnt[wv]; e0 += WAVE) {
+            const uint32_t e = e0 + lane;
+            const uint32_t key = e < s_cnt[wv] ? mag_key(s_cval[wv][e]) : 0u;
+            n_gt += popc64(__ballot(e < s_cnt[wv] && key > T));
+            n_eq += popc64(__ballot(e < s_cnt[wv] && key == T));
+        }
+        if (lane == 0) {
+            s_gt[wv] = n_gt;
+            s_eq[wv] = n_eq;
+        }
+        __syncthreads();
+        uint32_t g = 0, q = 0;  // selected-above and equal entries before this wave's share
+        for (uint32_t w = 0; w < wv; ++w) {
+            g += s_gt[w];
+            q += s_eq[w];
+        }
+        for (uint32_t e0 = 0; e0 < s_cnt[wv]; e0 += WAVE) {
+            const uint32_t e = e0 + lane;
+            const bool live = e < s_cnt[wv];
+            const uint32_t bits = live ? s_cval[wv][e] : 0u;
+            const uint32_t key = mag_key(bits);
+            const bool gt = live && key > T, eq = live && key == T;
+            const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
+            const uint32_t g_before = g + lanes_below(m_gt), q_before = q + lanes_below(m_eq);
+            if (gt || (eq && q_before < r)) {
+                const uint64_t pos = d.out_off + g_before + (q_before < r ? q_before : r);
+                out_idx[pos] = s_cidx[wv][e];
+                out_val[pos] = bits;
+            }
+            g += popc64(m_gt);
+            q += popc64(m_eq);
+        }
+        return;
+    }
+
+    // ordered write from the tensor: entry e goes to position #{selected entries before e}
+    uint32_t gt_before = 0, eq_before = 0;
+    for (uint32_t q0 = 0; q0 < nquads; q0 += SBLOCK) {
+        const uint32_t q = q0 + tid;
+        const uint4 v = q < nquads ? load4(d.g, q * 4, d.n, vec) : make_uint4(0, 0, 0, 0);
+        const uint32_t bits[4] = {v.x, v.y, v.z, v.w};
+        bool gt[4], eq[4];
+        uint32_t cnt = 0;
+#pragma unroll
+        for (uint32_t c = 0; c < 4; ++c) {
+            const uint32_t key = mag_key(bits[c]);
+            const bool valid = q < nquads && q * 4 + c < d.n;
+            gt[c] = valid && key > T;
+            eq[c] = valid && key == T;
+            cnt += (gt[c] ? 1u : 0u) + (eq[c] ? 0x10000u : 0u);
+        }
+        uint32_t tot;  // both counts in one scan: at most 4096 each per round
+        const uint32_t o = block_exclusive_scan<SWAVES>(cnt, s_wave, tot);
+        uint32_t g = gt_before + (o & 0xffffu), e = eq_before + (o >> 16);
+#pragma unroll
+        for (uint32_t c = 0; c < 4; ++c) {
+            if (gt[c]) {
+                const uint64_t pos = d.out_off + g + (e < r ? e : r);
+                out_idx[pos] = q * 4 + c;
+                out_val[pos] = bits[c];
+                ++g;
+            } else if (eq[c]) {
+                if (e < r) {
+                    const uint64_t pos = d.out_off + g + e;
+                    out_idx[pos] = q * 4 + c;
+                    out_val[pos] = bits[c];
+                }
+                ++e;
+            }
+        }
+        gt_before += tot & 0xffffu;
+        eq_before += tot >> 16;
+        if (gt_before + (eq_before < r ? eq_before : r) == d.k) break;  // uniform: all k written
+    }
+}
+
 // ---- chunk numbering across tensors ------------------------------------------------
 // The descent, count and emit kernels run with a fixed number of workgroups; each worker
 // (workgroup or wave) takes a contiguous range of the global chunk numbering.
@@ -976,15 +1280,24 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
     if (put_async(out->layer_off_dev, off.data(), off.size() * sizeof(uint64_t), s) != hipSuccess)
         return ADACOMP_ERR_HIP;
     if (L == 0) return ADACOMP_OK;
-    if (put_async(ws.desc, plan.desc.data(), plan.desc.size() * sizeof(LayerDesc), s) != hipSuccess)
-        return ADACOMP_ERR_HIP;
-    if (fill_u32_async(ws.hist, 0u, (size_t)L * BINS, s) != hipSuccess) return ADACOMP_ERR_HIP;
-
     const LayerDesc &tot = plan.desc[L];
     uint32_t *out_idx = out->idx;
     uint32_t *out_val = reinterpret_cast<uint32_t *>(out->val);
-    LAUNCH(ADACOMP_KERNEL_SAMPLE_HIST, k_sample_hist, tot.sblk_base, ws, L);
-    LAUNCH(ADACOMP_KERNEL_PICK, k_pick, L, ws);
+    if (!plan.small.empty()) {
+        if (put_async(ws.small, plan.small.data(), plan.small.size() * sizeof(SmallDesc), s) != hipSuccess)
+            return ADACOMP_ERR_HIP;
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_SMALL, k_small, dim3((unsigned)plan.small.size()), dim3(SBLOCK), s, ws.small,
+                       out_idx, out_val);
+        if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
+    }
+    if (tot.seg_base == 0 && tot.iblk_base == 0) return ADACOMP_OK;  // nothing for the pipeline
+    if (put_async(ws.desc, plan.desc.data(), plan.desc.size() * sizeof(LayerDesc), s) != hipSuccess)
+        return ADACOMP_ERR_HIP;
+    if (tot.seg_base) {
+        if (fill_u32_async(ws.hist, 0u, (size_t)L * BINS, s) != hipSuccess) return ADACOMP_ERR_HIP;
+        LAUNCH(ADACOMP_KERNEL_SAMPLE_HIST, k_sample_hist, tot.sblk_base, ws, L);
+        LAUNCH(ADACOMP_KERNEL_PICK, k_pick, L, ws);
+    }
     if (tot.sblk_base) {  // at least one tensor goes through the filter
         LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, tot.wblk_base, ws, L);
         LAUNCH(ADACOMP_KERNEL_CHECK, k_check, L, ws);

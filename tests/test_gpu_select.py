@@ -112,8 +112,10 @@ def test_adversarial_ties_at_threshold(ac, dev, rate):
     check(ac, g, rate, what="adversarial ties")
 
 
-def test_degenerate_tensors(ac, dev):
-    n = 300_007
+@pytest.mark.parametrize("n", [300_007, 70_001, 4_099])
+def test_degenerate_tensors(ac, dev, n):
+    """Constant magnitudes, all zeros, strictly monotone ramps, two levels, special values: at a size
+    that goes through the streaming pipeline and at sizes one workgroup selects on its own."""
     ones = torch.ones(n, device=dev)
     ones[::3] = -1.0
     zeros = torch.zeros(n, device=dev)
@@ -203,3 +205,32 @@ def test_whole_model_selection_is_select_on_one_tensor(ac, dev):
                                  for l in range(len(g))])
     whole = u.idx[:u.total].cpu().numpy().view(np.uint32).astype(np.int64)
     assert whole.size != per_global.size or not np.array_equal(whole, per_global)
+
+
+def test_small_tensors_through_the_streaming_pipeline(ac, dev, monkeypatch):
+    """With the one-workgroup path switched off, small tensors take the pipeline built for large
+    ones; both must give the oracle's selection."""
+    monkeypatch.setenv("ADACOMP_SELECT_SMALL", "0")
+    g = workloads.gradient("paper_cnn", 1, device=dev)
+    for rate in (0.1, 0.01, 0.0001):
+        check(ac, g, rate, what="paper_cnn, pipeline")
+    sizes = workloads.sizes_of("adversarial")
+    pick = [l for l, n in enumerate(sizes) if n < 300_000][:6]
+    check(ac, [workloads.gradient_layer("adversarial", 0, l, sizes[l], dev) for l in pick], 0.02, what="adversarial, pipeline")
+    monkeypatch.delenv("ADACOMP_SELECT_SMALL")
+    check(ac, g, 0.01, what="paper_cnn, one workgroup per tensor")
+
+
+def test_many_small_tensors_ties_and_unaligned(ac, dev):
+    """600 small tensors of ragged sizes cut out of one buffer (most start off a 16-byte boundary),
+    values quantised to a few levels so that every threshold falls inside a run of equal magnitudes."""
+    gen = torch.Generator(device=dev).manual_seed(23)
+    base = (torch.randn(3_000_000, generator=gen, device=dev) * 4).round() / 4       # multiples of 0.25
+    sizes = torch.randint(1, 9000, (600,), generator=torch.Generator().manual_seed(5)).tolist()
+    sizes[17], sizes[18] = 262_144, 262_143
+    tensors, at = [], 1
+    for n in sizes:
+        tensors.append(base[at:at + n])
+        at += n + 1
+    for rate in (0.003, 0.05, 0.5):
+        check(ac, tensors, rate, what="many small")
