@@ -8,6 +8,9 @@ over all of them (one call over the 1600 tensors by default, or 16 calls with
 --per-gradient-calls), then one adacomp_apply of the 16-update queue.
 value = gradient elements compressed and applied per second = 16e9 / step time.
 
+--workload paper_cnn runs the same step on the network size and worker count of the paper's own
+experiments (211,690 parameters, 200 workers): a latency regime, reported the same way.
+
 Prints ONE JSON line.  `roofline` is for the dominant kernel (select's streaming filter
 pass), timed live with HIP events on the launch stream inside the timed steps;
 `cpu_baseline` is the CPU oracle as it stands, single thread, on a bounded sample.
@@ -26,23 +29,29 @@ HBM_PEAK_GBS = 8000.0
 
 
 def cpu_baseline(cfg, rate, lr, pulls, n_updates=4, layer=0):
-    """Oracle select + apply of `n_updates` worker updates on one 10M-entry tensor."""
+    """Oracle select + apply of `n_updates` worker updates: on one 10M-entry tensor of the flat
+    workload, on the whole model of the small one."""
     import numpy as np
 
     import oracle
     import workloads
 
-    grads = [workloads.gradient_layer(cfg, q, layer).numpy() for q in range(n_updates)]
-    theta = [workloads.theta0(cfg, layers=[layer])[0].numpy().copy()]
+    whole = cfg != "flat"
+    layers = list(range(len(workloads.sizes_of(cfg)))) if whole else [layer]
+    if whole:
+        n_updates = len(pulls)
+    grads = [[workloads.gradient_layer(cfg, q, l).numpy() for l in layers] for q in range(n_updates)]
+    theta = [t.numpy().copy() for t in workloads.theta0(cfg, layers=layers)]
     ps = oracle.ParameterServer(theta)
     t0 = time.perf_counter()
     for q in range(n_updates):
-        off, idx, val = oracle.select([grads[q]], rate)
+        off, idx, val = oracle.select(grads[q], rate)
         ps.apply(off, idx, val, min(pulls[q], q), lr)
     dt = time.perf_counter() - t0
-    elems = n_updates * grads[0].size
+    elems = n_updates * sum(g.size for g in grads[0])
+    what = "the whole model" if whole else "one 10M-entry tensor"
     return {"value": elems / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
-            "sample": f"{n_updates} worker updates of one 10M-entry tensor of the flat workload "
+            "sample": f"{n_updates} worker updates of {what} of the {cfg} workload "
                       f"(select at {rate}, then PS apply), {dt:.1f} s of single-thread C"}
 
 
@@ -57,6 +66,10 @@ def main():
                     help="one adacomp_select call per worker gradient instead of one call over all 16")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the 16 independent selects of a step are spread over (each has its own workspace)")
+    ap.add_argument("--workload", default="flat", choices=["flat", "paper_cnn"],
+                    help="flat: the roofline configuration (default, the one the metric is quoted on); paper_cnn: the "
+                         "211,690-parameter network and 200 workers of the paper's experiments (latency regime)")
+    ap.add_argument("--rate", type=float, default=None, help="compression ratio c (default: the workload's first)")
     ap.add_argument("--wire", action="store_true",
                     help="also encode / decode one worker update in the wire format and report bytes and times")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -74,9 +87,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
-    cfg = "flat"
+    cfg = args.workload
     c = workloads.CONFIGS[cfg]
-    rate, lr, Q = c["rates"][0], c["lr"], c["Q"]
+    rate, lr, Q = (c["rates"][0] if args.rate is None else args.rate), c["lr"], c["Q"]
+    small = cfg == "paper_cnn"      # every tensor is selected by one workgroup (k_small), not streamed by k_filter
     sizes = workloads.sizes_of(cfg)
     L, N = len(sizes), sum(sizes)
     pulls = workloads.pull_timestamps(workloads.staleness(cfg))
@@ -100,12 +114,14 @@ def main():
         # the C ABI takes any list of tensors: all 16 worker gradients (1600 tensors) go through ONE
         # select call, so the small per-call kernels are paid once; its output buffers are then
         # viewed as the 16 worker updates (100 tensors each, own pull timestamp) that apply takes
-        all_tensors = [t for g in grads for t in g]
+        all_tensors = ac.Layers([t for g in grads for t in g])     # marshalled once
         big = ac.Update(L * Q, cap * Q, dev)
         sel_wss = [torch.empty(ac.adacomp_select_workspace(sizes * Q, rate), dtype=torch.uint8, device=dev)]
         ac.adacomp_select(all_tensors, rate, big, sel_wss[0])
         updates = [big.view(q * L, (q + 1) * L) for q in range(Q)]
-    app_ws = torch.empty(ac.adacomp_apply_workspace(sizes, updates), dtype=torch.uint8, device=dev)
+    app_ws = torch.empty(max(256, ac.adacomp_apply_workspace(sizes, updates)), dtype=torch.uint8, device=dev)
+    params = ac.Layers(theta)          # marshalled once, like the queue
+    queue = ac.Queue(updates)
     torch.cuda.synchronize()
 
     main = torch.cuda.current_stream(dev)
@@ -131,9 +147,9 @@ def main():
 
     def step():
         selects()
-        ac.adacomp_apply(theta, state, updates, lr, app_ws)
+        ac.adacomp_apply(params, state, queue, lr, app_ws)
 
-    if args.copy_calibration:     # reads 4e9 bytes, writes 4e9 bytes
+    if args.copy_calibration and not small:     # reads 4e9 bytes, writes 4e9 bytes
         src = torch.cat([g.view(-1) for g in grads[0]])
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
@@ -144,7 +160,8 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ac.adacomp_profile_start({"filter"})
+    dominant = "small" if small else "filter"
+    ac.adacomp_profile_start({dominant})
     t_begin = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -156,7 +173,7 @@ def main():
     ms_per_step = 1e3 * sec / args.steps
     value = Q * N * args.steps / sec
 
-    f_ms, f_n = prof["filter"]
+    f_ms, f_n = prof[dominant]
     f_avg_s = 1e-3 * f_ms / f_n
     per_launch = Q if batched else 1          # worker gradients one filter launch streams through
     # per launch: every element read once, every selected pair written
@@ -164,7 +181,7 @@ def main():
     achieved = alg_bytes / f_avg_s / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "filter_flat_traffic.json")
-    if os.path.exists(tpath):   # HBM bytes per launch from the committed rocprofv3 --pmc summary
+    if os.path.exists(tpath) and not small:   # HBM bytes per launch from the committed rocprofv3 --pmc summary
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch_batched" if batched else "hbm_bytes_per_launch")
     out = {
@@ -172,12 +189,16 @@ def main():
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "flat: 100 tensors x 10M fp32 = 1e9 elements per worker gradient, "
-                               "95% N(0,1e-5) + 5% N(0,1e-2), rate 0.5% per tensor, 16 queued updates, "
-                               "staleness U[1,16]; step = select of the 16 worker gradients + 1 apply of the queue",
+        "config": {"workload": ("flat: 100 tensors x 10M fp32 = 1e9 elements per worker gradient, "
+                                "95% N(0,1e-5) + 5% N(0,1e-2), rate 0.5% per tensor, 16 queued updates, "
+                                "staleness U[1,16]; step = select of the 16 worker gradients + 1 apply of the queue")
+                   if not small else
+                   (f"paper_cnn: 8 tensors, 211,690 fp32 parameters (Sec. 5.1), heavy-tailed gradients, rate {rate} per "
+                    "tensor, 200 queued worker updates, staleness U[1,200]; step = select of the 200 worker gradients "
+                    "+ 1 apply of the queue (latency regime: microseconds of work per launch)"),
                    "select_calls_per_step": 1 if batched else Q, "select_streams": ns,
                    "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q},
-        "roofline": {"bound": "hbm", "kernel": "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "k_small" if small else "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": 1e3 * f_avg_s,
                      "launches": f_n},
@@ -191,7 +212,7 @@ def main():
     ev[0].record()
     selects()
     ev[1].record()
-    ac.adacomp_apply(theta, state, updates, lr, app_ws)
+    ac.adacomp_apply(params, state, queue, lr, app_ws)
     ev[2].record()
     torch.cuda.synchronize()
     if args.breakdown:

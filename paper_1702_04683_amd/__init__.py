@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     AdaCompError,
     Update,
     Layers,
+    Queue,
     State,
     adacomp_count,
     adacomp_select_workspace,

@@ -224,6 +224,32 @@ class Layers:
         return len(self.tensors)
 
 
+class Queue:
+    """A list of Updates marshalled once (adacomp_update_t array) for repeated apply calls on the
+    same buffers; only the pull timestamps are refreshed on every call."""
+
+    def __init__(self, updates):
+        self.updates = list(updates)
+        self._arr = (_Update * max(len(self.updates), 1))(*[u.c_struct() for u in self.updates])
+
+    def __len__(self):
+        return len(self.updates)
+
+    def __iter__(self):
+        return iter(self.updates)
+
+    def _refresh(self):
+        for q, u in enumerate(self.updates):
+            self._arr[q].pull_ts = u.pull_ts
+        return self._arr
+
+
+def _updates(updates):
+    if isinstance(updates, Queue):
+        return updates._refresh()
+    return (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
+
+
 def _layers(tensors):
     if isinstance(tensors, Layers):
         return tensors._arr
@@ -253,7 +279,7 @@ def adacomp_apply_workspace(sizes, updates, state=None):
     """Workspace bytes for applying `updates` to parameter tensors of the given sizes (state:
     the State they will be applied to; None = a fresh one)."""
     out = C.c_size_t(0)
-    arr = (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
+    arr = _updates(updates)
     rc = load_library().adacomp_apply_workspace(_u64_array(sizes), len(sizes),
                                                 C.byref(state._c) if state is not None else None,
                                                 arr, len(updates), C.byref(out))
@@ -265,7 +291,7 @@ def adacomp_apply_workspace(sizes, updates, state=None):
 def adacomp_apply(params, state, updates, lr, workspace, stream=None):
     """Apply a queue of Updates to the parameter tensors in place.  Asynchronous."""
     dev = workspace.device
-    arr = (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
+    arr = _updates(updates)
     rc = load_library().adacomp_apply(_layers(params), len(params), C.byref(state._c), arr, len(updates),
                                       float(lr), workspace.data_ptr(),
                                       workspace.numel() * workspace.element_size(), _stream_ptr(stream, dev))
@@ -278,7 +304,7 @@ def adacomp_apply(params, state, updates, lr, workspace, stream=None):
 def adacomp_apply_global_staleness(params, state, updates, lr, workspace, stream=None):
     """The competitors' rule (one learning rate per update, lr / global staleness).  Asynchronous."""
     dev = workspace.device
-    arr = (_Update * max(len(updates), 1))(*[u.c_struct() for u in updates])
+    arr = _updates(updates)
     rc = load_library().adacomp_apply_global_staleness(
         _layers(params), len(params), C.byref(state._c), arr, len(updates), float(lr), workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), _stream_ptr(stream, dev))
