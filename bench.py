@@ -175,15 +175,17 @@ def main():
 
     f_ms, f_n = prof[dominant]
     f_avg_s = 1e-3 * f_ms / f_n
-    per_launch = Q if batched else 1          # worker gradients one filter launch streams through
-    # per launch: every element read once, every selected pair written
-    alg_bytes = per_launch * (4.0 * N + 8.0 * cap)
+    # every element read once, every selected pair written; a step's worker gradients go through the
+    # kernel in one or more launches (the library groups tensors so that a group's candidates stay cached)
+    launches_per_step = f_n / args.steps
+    alg_bytes = Q * (4.0 * N + 8.0 * cap) / launches_per_step
     achieved = alg_bytes / f_avg_s / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "filter_flat_traffic.json")
-    if os.path.exists(tpath) and not small:   # HBM bytes per launch from the committed rocprofv3 --pmc summary
+    if os.path.exists(tpath) and not small:   # HBM bytes per step from the committed rocprofv3 --pmc summary
         with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch_batched" if batched else "hbm_bytes_per_launch")
+            per_step = json.load(f).get("hbm_bytes_per_step")
+        traffic = per_step / launches_per_step if per_step else None
     out = {
         "metric": "gradient elements/sec compressed+applied",
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
