@@ -36,7 +36,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = C.CDLL(build())
+        # ADACOMP_ORACLE_LIB: load that build instead (tests/test_oracle_mutants.py points it at
+        # deliberately broken copies to show that the pins notice)
+        lib = C.CDLL(os.environ.get("ADACOMP_ORACLE_LIB") or build())
         u64, u32, f64, vp = C.c_uint64, C.c_uint32, C.c_double, C.c_void_p
         lib.adacomp_oracle_count.restype = u64
         lib.adacomp_oracle_count.argtypes = [u64, f64]
