@@ -23,6 +23,12 @@
  *     checked before anything is enqueued: a failing call has no side effect.
  *   - Sizes are in elements unless a name says bytes.  A tensor has at most
  *     2^32 - 1 elements.  Zero-element tensors are legal.
+ *   - Environment switches, read at every call; they choose between execution plans that
+ *     give identical results and exist for tests and measurements:
+ *       ADACOMP_APPLY_PLAN=scatter|sweep   force one plan of adacomp_apply
+ *       ADACOMP_SELECT_SMALL=0             small tensors take the streaming pipeline too
+ *       ADACOMP_SELECT_GROUP_MB=<n>        candidate-region size per group of tensors (0: one group)
+ *     The *_workspace call and the call it sizes must see the same values.
  */
 #ifndef ADACOMP_H
 #define ADACOMP_H
