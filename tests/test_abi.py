@@ -157,3 +157,65 @@ def test_wire_host_side_checks(lib):
     with pytest.raises(ac.AdaCompError) as e:
         ac.adacomp_wire_bound([0, 1 << 33])
     assert e.value.code == -3
+
+
+def test_global_staleness_validate_and_wire_argument_checks_run_before_any_launch(lib):
+    """Every failing call below must fail on the host (no GPU here) and leave the state untouched."""
+    off = (C.c_uint64 * 2)(0, 3)
+    par = (binding._Layer * 1)()
+    par[0].data, par[0].n = 0x1000, 100
+    st = binding._State(5, 1, None)                         # the competitors' rule needs no counters
+    upd = (binding._Update * 1)()
+    upd[0] = binding._Update(1, C.cast(off, C.POINTER(C.c_uint64)), 0x2000, 0x3000, 0x4000, 3, 5)
+    call = lambda lr=0.1, ws=0x10000, nb=1 << 12: lib.adacomp_apply_global_staleness(par, 1, C.byref(st), upd, 1, lr, ws, nb,
+                                                                                       None)
+    upd[0].pull_ts = 6
+    assert call() == -7
+    upd[0].pull_ts = 0                                      # any earlier pull is fine for this rule ...
+    assert call(ws=None) == -5                              # ... so the next check is the workspace
+    assert call(nb=8) == -5
+    assert call(ws=0x10010) == -5
+    assert call(lr=float("nan")) == -10
+    upd[0].cap = 2
+    assert call() == -4
+    upd[0].cap = 3
+    upd[0].val = 0x4002
+    assert call() == -11
+    upd[0].val = 0x4000
+    st.num_layers = 3
+    assert call() == -6
+    st.num_layers = 1
+    assert st.t == 5
+
+    v = lambda u, n=0x6000, L=1, flags=0x7000: lib.adacomp_update_validate(C.byref(u), n, L, flags, None)
+    assert v(upd[0], flags=None) == -1
+    assert v(upd[0], n=None) == -1
+    assert v(upd[0], L=2) == -6
+    assert v(upd[0], flags=0x7002) == -11
+    upd[0].cap = 1
+    assert v(upd[0]) == -4
+    upd[0].cap = 3
+
+    words = C.c_uint64()
+    pack = lambda u, wire=0x8000, cap=1 << 20, out=0x9000, ws=0x10000, nb=1 << 12: lib.adacomp_wire_pack(
+        C.byref(u), wire, cap, out, ws, nb, None)
+    assert pack(upd[0], out=None) == -1
+    assert pack(upd[0], wire=None) == -1
+    assert pack(upd[0], wire=0x8002) == -11
+    assert pack(upd[0], out=0x9004) == -11
+    assert pack(upd[0], ws=None) == -5
+    assert pack(upd[0], nb=16) == -5
+    upd[0].cap = 2
+    assert pack(upd[0]) == -4
+    upd[0].cap = 3
+    unpack = lambda u, wire=0x8000, n=100, flags=0x7000, ws=0x10000, nb=1 << 12: lib.adacomp_wire_unpack(
+        wire, n, C.byref(u), flags, ws, nb, None)
+    assert unpack(upd[0], flags=None) == -1
+    assert unpack(upd[0], wire=None) == -1
+    assert unpack(upd[0], wire=0x8001) == -11
+    assert unpack(upd[0], ws=0x10000, nb=0) == -5
+    off[1] = 4                                              # the receiver expects more entries than the buffers hold
+    assert unpack(upd[0]) == -4
+    off[1] = 3
+    assert lib.adacomp_wire_bound(off, 1, C.byref(words)) == 0 and words.value == 4 + 1 + 1 + 1 + 3 + 3
+    assert lib.adacomp_wire_bound(off, 1, None) == -1
