@@ -70,6 +70,9 @@ def main():
                     help="flat: the roofline configuration (default, the one the metric is quoted on); paper_cnn: the "
                          "211,690-parameter network and 200 workers of the paper's experiments (latency regime)")
     ap.add_argument("--rate", type=float, default=None, help="compression ratio c (default: the workload's first)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step in a HIP graph and time replays of it (the kernel timing for `roofline` then "
+                         "comes from the same number of eager steps run afterwards)")
     ap.add_argument("--wire", action="store_true",
                     help="also encode / decode one worker update in the wire format and report bytes and times")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -161,13 +164,32 @@ def main():
         step()
     torch.cuda.synchronize()
     dominant = "small" if small else "filter"
-    ac.adacomp_profile_start({dominant})
-    t_begin = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t_end = time.perf_counter()
-    prof = ac.adacomp_profile_stop()
+    if args.graph:
+        # a recorded step fixes addresses, sizes and the pulls relative to the queue: exactly what every step
+        # of this bench repeats.  Replays need no host work beyond one launch.
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t_end = time.perf_counter()
+        ac.adacomp_profile_start({dominant})
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        prof = ac.adacomp_profile_stop()
+    else:
+        ac.adacomp_profile_start({dominant})
+        t_begin = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t_end = time.perf_counter()
+        prof = ac.adacomp_profile_stop()
 
     sec = t_end - t_begin
     ms_per_step = 1e3 * sec / args.steps
@@ -198,7 +220,7 @@ def main():
                    (f"paper_cnn: 8 tensors, 211,690 fp32 parameters (Sec. 5.1), heavy-tailed gradients, rate {rate} per "
                     "tensor, 200 queued worker updates, staleness U[1,200]; step = select of the 200 worker gradients "
                     "+ 1 apply of the queue (latency regime: microseconds of work per launch)"),
-                   "select_calls_per_step": 1 if batched else Q, "select_streams": ns,
+                   "select_calls_per_step": 1 if batched else Q, "select_streams": ns, "hip_graph": bool(args.graph),
                    "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q},
         "roofline": {"bound": "hbm", "kernel": "k_small" if small else "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

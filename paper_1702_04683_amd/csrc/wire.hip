@@ -23,7 +23,7 @@ namespace {
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t WAVES = BLOCK / WAVE;
 constexpr uint32_t SCAN_BLOCK = 1024;
-constexpr uint32_t SCAN_ITEMS = 4;
+constexpr uint32_t SCAN_ITEMS = 4;   // consecutive counts per thread and round of the single-workgroup scan (16 was slower)
 constexpr uint32_t MAGIC = 0x31434441u;
 
 struct Wire {
