@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-def cpu_baseline(cfg, rate, lr, pulls, n_updates=4, layer=0):
+def cpu_baseline(cfg, rate, lr, pulls, n_updates=16, layer=0):
     """Oracle select + apply of `n_updates` worker updates: on one 10M-entry tensor of the flat
     workload, on the whole model of the small one."""
     import numpy as np

@@ -24,6 +24,9 @@
 //   7. count / scan / emit  per-chunk counts of key > T and key == T, their exclusive
 //                         scans, and the order-preserving write of exactly k
 //                         (index, value) pairs.
+// Steps 3-5 are launched once per group of consecutive tensors; all groups use the same
+// candidate-region memory, sized so that what a group writes there is still in the
+// last-level cache when its gather reads it.
 // Tensors with k == n are copied (identity), tensors with k == 0 produce nothing,
 // tensors with k > n/8 skip steps 1-5.
 //
