@@ -46,6 +46,7 @@ constexpr uint32_t TILE_MAX = 2048;    // sweep plan: most coordinates per tile 
 constexpr uint32_t STAGE_CAP = 512;    // sweep plan: entries of the whole queue a tile can hold in LDS
 constexpr uint32_t SLOW_GRID = 1024;
 constexpr uint32_t PASS = 256;           // sweep plan: updates whose slices are staged together
+constexpr uint32_t PASS_SHORT = 32;      // sweep plan: longest queue the kernel for short queues takes
 // one launch costs about as much as this many bytes of memory traffic (4 us at 5 TB/s)
 constexpr double LAUNCH_COST_BYTES = 20e6;
 static_assert((TILE_MAX & (TILE_MAX - 1)) == 0 && TILE_MAX >= BLOCK && STAGE_CAP % BLOCK == 0 && STAGE_CAP <= 65535,
@@ -263,20 +264,37 @@ struct Slices {
     uint32_t tag[PASS];          // update number | staleness inside the call << 15 (key bits of its touches)
 };
 
+// The bounds of the calling thread's update in a tile, fetched by the kernel ahead of time for a
+// queue of at most PASS updates (then thread q serves update q in every tile of the workgroup).
+struct Fetched {
+    bool valid;   // bounds are in b0 / b1
+    bool first;   // first tile of the workgroup: the update's arrays are not yet in `sl`
+    uint32_t b0, b1;
+};
+
 __device__ __forceinline__ uint32_t load_slices(const Sweep &sw, uint32_t t, uint32_t q0, Slices &sl,
-                                                uint32_t *s_wave) {
+                                                uint32_t *s_wave, const Fetched &f) {
     const uint32_t q = q0 + threadIdx.x;
     const bool mine = threadIdx.x < PASS && q < sw.Q;
     uint32_t b0 = 0, len = 0;
     if (mine) {
-        const uint32_t *row = sw.B + (uint64_t)q * (sw.ntiles + 1) + t;
-        const UpdDesc u = sw.U[q];
-        b0 = row[0];
-        len = row[1] >= b0 ? row[1] - b0 : 0u;  // bounds of an unsorted (malformed) list may cross
-        sl.idx[threadIdx.x] = u.idx;
-        sl.val[threadIdx.x] = u.val;
-        sl.pre[threadIdx.x] = u.pre;
-        sl.tag[threadIdx.x] = q | ((q - u.pull) << 15);
+        uint32_t b1;
+        if (f.valid) {
+            b0 = f.b0;
+            b1 = f.b1;
+        } else {
+            const uint32_t *row = sw.B + (uint64_t)q * (sw.ntiles + 1) + t;
+            b0 = row[0];
+            b1 = row[1];
+        }
+        len = b1 >= b0 ? b1 - b0 : 0u;  // bounds of an unsorted (malformed) list may cross
+        if (!f.valid || f.first) {
+            const UpdDesc u = sw.U[q];
+            sl.idx[threadIdx.x] = u.idx;
+            sl.val[threadIdx.x] = u.val;
+            sl.pre[threadIdx.x] = u.pre;
+            sl.tag[threadIdx.x] = q | ((q - u.pull) << 15);
+        }
     }
     uint32_t total;
     const uint32_t o = block_exclusive_scan<WAVES>(len, s_wave, total);
@@ -305,7 +323,7 @@ __device__ __forceinline__ uint32_t slot(uint32_t c) { return c + (c >> 4); }
 // staleness field is q - pull for an update pulled inside the call; for one pulled earlier
 // its window covers the whole call so far, and the field holds the staleness it had
 // accumulated before the call.
-__global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
+__device__ __forceinline__ void sweep_tile(const Sweep &sw, const uint32_t t, const Fetched &fetched) {
     // per coordinate: count, then start, then end of its list; slot(c) skews the index so
     // that the scan's 16-consecutive-per-thread accesses fall into distinct banks
     __shared__ uint32_t s_cur[TILE_MAX + TILE_MAX / 16];
@@ -317,7 +335,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
     __shared__ uint32_t s_wave[WAVES];
     __shared__ uint32_t s_bad;
 
-    const uint32_t t = blockIdx.x, tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x;
     const uint32_t tile = 1u << sw.tile_shift;
     const ParamDesc pd = sw.P[sw.tile_tensor[t]];
     const uint32_t c0 = (t - (uint32_t)pd.tile_base) << sw.tile_shift;
@@ -338,7 +356,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
     float v[PER_THREAD];
     uint32_t total = 0;
     for (uint32_t q0 = 0; q0 < sw.Q; q0 += PASS) {
-        const uint32_t n_pass = load_slices(sw, t, q0, sl, s_wave);
+        const uint32_t n_pass = load_slices(sw, t, q0, sl, s_wave, fetched);
         const uint32_t n_slices = sw.Q - q0 < PASS ? sw.Q - q0 : PASS;
         total += n_pass;
         if (total > STAGE_CAP) break;  // uniform
@@ -393,7 +411,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
     for (uint32_t q0 = 0; q0 < sw.Q; q0 += PASS) {
         uint32_t n_pass = total;
         if (sw.Q > PASS) {  // several passes: fetch this pass's entries again (cache hits)
-            n_pass = load_slices(sw, t, q0, sl, s_wave);
+            n_pass = load_slices(sw, t, q0, sl, s_wave, fetched);
             const uint32_t n_slices = sw.Q - q0 < PASS ? sw.Q - q0 : PASS;
 #pragma unroll
             for (uint32_t j = 0; j < PER_THREAD; ++j) {
@@ -462,6 +480,225 @@ __global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
         float th = theta[j];
         for (uint32_t m = lo[j]; m < hi[j]; ++m) th = __fsub_rn(th, s_prod[m]);
         pd.theta[c0 + coord[j]] = th;
+    }
+}
+
+// A workgroup takes TPB consecutive tiles, one after the other.  A tile is a few microseconds
+// of work behind a chain of dependent loads (bounds -> entries -> parameters); with a queue
+// of at most PASS updates thread q fetches the bounds of update q for all TPB tiles at once
+// (they are neighbours in memory) and the update's descriptor once, which takes the first
+// link of the chain off all tiles but the first.
+template <uint32_t TPB>
+__global__ __launch_bounds__(BLOCK) void k_sweep(Sweep sw) {
+    const uint32_t t0 = blockIdx.x * TPB;
+    const bool ahead = sw.Q <= PASS;
+    uint32_t row[TPB + 1];
+    if (ahead && threadIdx.x < sw.Q) {
+        const uint32_t *b = sw.B + (uint64_t)threadIdx.x * (sw.ntiles + 1) + t0;
+#pragma unroll
+        for (uint32_t i = 0; i <= TPB; ++i) row[i] = t0 + i <= sw.ntiles ? b[i] : 0u;
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+        const uint32_t t = t0 + i;
+        if (t >= sw.ntiles) return;
+        sweep_tile(sw, t, Fetched{ahead, i == 0, row[i], row[i + 1]});
+        __syncthreads();  // the next tile reuses the LDS arrays
+    }
+}
+
+// The same sweep for queues of at most PASS_SHORT updates, arranged so that the chain of
+// dependent loads (bounds -> entries -> parameters) is paid once per workgroup instead of
+// once per tile: wave 0 fetches the bounds of every update in all TPB tiles and scans them
+// with lane shuffles; then every thread requests its entries of all TPB tiles together, then
+// the parameters those entries touch; only then the tiles are sorted and replayed one after
+// the other out of registers and LDS.
+template <uint32_t TPB>
+__global__ __launch_bounds__(BLOCK) void k_sweep_short(Sweep sw) {
+    constexpr uint32_t QS = PASS_SHORT;
+    __shared__ uint32_t s_cur[TILE_MAX + TILE_MAX / 16];
+    __shared__ uint32_t s_key[STAGE_CAP];
+    __shared__ float s_val[STAGE_CAP];
+    __shared__ float s_theta[STAGE_CAP];     // Theta of the touch's coordinate, as fetched ahead
+    __shared__ float s_prod[STAGE_CAP];
+    __shared__ uint16_t s_coord[STAGE_CAP];
+    __shared__ const uint32_t *s_idx[QS];
+    __shared__ const float *s_valp[QS];
+    __shared__ const uint32_t *s_pre[QS];
+    __shared__ uint32_t s_tag[QS];
+    __shared__ uint32_t s_off[TPB][QS + 1];  // per tile: staged position of the first entry of update q; [Q..QS] = entries
+    __shared__ uint32_t s_b0[TPB][QS];
+    __shared__ uint32_t s_wave[WAVES];
+    __shared__ uint32_t s_bad[TPB];
+
+    const uint32_t tid = threadIdx.x, t0 = blockIdx.x * TPB;
+    const uint32_t tile = 1u << sw.tile_shift;
+    const uint32_t per_thread = tile >= BLOCK ? tile / BLOCK : 1u;
+    const bool scans = tid * per_thread < tile;
+
+    // the tiles' tensors (independent of the bounds: both requests are in flight together)
+    uint32_t tensor[TPB];
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) tensor[i] = t0 + i < sw.ntiles ? sw.tile_tensor[t0 + i] : 0u;
+
+    if (tid < WAVE) {  // wave 0: bounds, their scans, the updates' arrays
+        const bool mine = tid < sw.Q;
+        uint32_t row[TPB + 1];
+        if (mine) {
+            const uint32_t *b = sw.B + (uint64_t)tid * (sw.ntiles + 1) + t0;
+#pragma unroll
+            for (uint32_t i = 0; i <= TPB; ++i) row[i] = t0 + i <= sw.ntiles ? b[i] : 0u;
+            const UpdDesc u = sw.U[tid];
+            s_idx[tid] = u.idx;
+            s_valp[tid] = u.val;
+            s_pre[tid] = u.pre;
+            s_tag[tid] = tid | ((tid - u.pull) << 15);
+        }
+#pragma unroll
+        for (uint32_t i = 0; i < TPB; ++i) {
+            // bounds of an unsorted (malformed) list may cross
+            const uint32_t len = (mine && t0 + i < sw.ntiles && row[i + 1] >= row[i]) ? row[i + 1] - row[i] : 0u;
+            uint32_t incl = len;
+#pragma unroll
+            for (int d = 1; d < WAVE; d <<= 1) {
+                const uint32_t y = __shfl_up(incl, d);
+                if (tid >= (uint32_t)d) incl += y;
+            }
+            if (tid <= QS) s_off[i][tid] = incl - len;  // lanes Q .. QS hold the total
+            if (mine) s_b0[i][tid] = row[i];
+        }
+    }
+    if (tid < TPB) s_bad[tid] = 0;
+    __syncthreads();
+
+    float *theta_of[TPB];  // first parameter of the tile
+    uint32_t c0[TPB], ncoord[TPB], total[TPB];
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+        const ParamDesc pd = sw.P[tensor[i]];
+        c0[i] = (t0 + i - (uint32_t)pd.tile_base) << sw.tile_shift;
+        ncoord[i] = pd.n - c0[i] < tile ? (uint32_t)(pd.n - c0[i]) : tile;
+        theta_of[i] = pd.theta + c0[i];
+        total[i] = s_off[i][QS];
+    }
+
+    // every entry of every tile of the workgroup: requested together
+    uint32_t c[TPB][PER_THREAD], key[TPB][PER_THREAD];
+    float v[TPB][PER_THREAD], th[TPB][PER_THREAD];
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+#pragma unroll
+        for (uint32_t j = 0; j < PER_THREAD; ++j) {
+            const uint32_t p = tid + j * BLOCK;
+            c[i][j] = 0xffffffffu;
+            v[i][j] = 0.f;
+            key[i][j] = 0;
+            if (total[i] <= STAGE_CAP && p < total[i]) {
+                const uint32_t u = slice_of(s_off[i], sw.Q, p);
+                const uint32_t e = s_b0[i][u] + (p - s_off[i][u]);
+                c[i][j] = s_idx[u][e] - c0[i];
+                v[i][j] = s_valp[u][e];
+                key[i][j] = s_tag[u];
+                if (s_pre[u]) {
+                    const uint32_t before = s_pre[u][e];
+                    if (before > 0x7fffu) s_bad[i] = 1;  // does not fit the key: leave the tile to the slow kernel
+                    key[i][j] = (key[i][j] & 0x7fffu) | (before << 15) | 0x40000000u;
+                }
+            }
+        }
+    }
+    // the parameters they touch: requested together as well
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+#pragma unroll
+        for (uint32_t j = 0; j < PER_THREAD; ++j) {
+            th[i][j] = 0.f;
+            if (c[i][j] < ncoord[i]) th[i][j] = theta_of[i][c[i][j]];
+        }
+    }
+
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+        if (t0 + i >= sw.ntiles || total[i] == 0) continue;  // uniform
+        for (uint32_t x = tid; x < tile + tile / 16; x += BLOCK) s_cur[x] = 0;
+        __syncthreads();
+        if (total[i] <= STAGE_CAP) {
+#pragma unroll
+            for (uint32_t j = 0; j < PER_THREAD; ++j) {
+                if (tid + j * BLOCK >= total[i]) continue;
+                if (c[i][j] >= ncoord[i]) s_bad[i] = 1;  // only a malformed (unsorted) index list gets here
+                else atomicAdd(&s_cur[slot(c[i][j])], 1u);
+            }
+        }
+        __syncthreads();
+        if (total[i] > STAGE_CAP || s_bad[i]) {  // leave the tile untouched for the slow kernel
+            if (tid == 0) sw.ovf[1 + atomicAdd(&sw.ovf[0], 1u)] = t0 + i;
+            continue;
+        }
+        {  // counts -> list starts
+            uint32_t sum = 0;
+            if (scans)
+                for (uint32_t j = 0; j < per_thread; ++j) sum += s_cur[slot(tid * per_thread + j)];
+            uint32_t all;
+            uint32_t run = block_exclusive_scan<WAVES>(sum, s_wave, all);
+            if (scans)
+                for (uint32_t j = 0; j < per_thread; ++j) {
+                    const uint32_t n_touch = s_cur[slot(tid * per_thread + j)];
+                    s_cur[slot(tid * per_thread + j)] = run;
+                    run += n_touch;
+                }
+            __syncthreads();
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < PER_THREAD; ++j) {  // group the touches by coordinate
+            if (tid + j * BLOCK >= total[i]) continue;
+            const uint32_t pos = atomicAdd(&s_cur[slot(c[i][j])], 1u);
+            s_key[pos] = key[i][j] | (is_nonzero(v[i][j]) ? 0x80000000u : 0u);
+            s_val[pos] = v[i][j];
+            s_theta[pos] = th[i][j];
+            s_coord[pos] = (uint16_t)c[i][j];
+        }
+        __syncthreads();
+        // per touch: rank in time, sigma (eq. 3), alpha_k * value (eq. 5 and the multiply of eq. 4)
+        float theta[PER_THREAD];
+        uint32_t lo[PER_THREAD], hi[PER_THREAD], coord[PER_THREAD];
+#pragma unroll
+        for (uint32_t j = 0; j < PER_THREAD; ++j) {
+            const uint32_t x = tid + j * BLOCK;
+            lo[j] = hi[j] = 0;
+            if (x >= total[i]) continue;
+            const uint32_t kx = s_key[x], cx = s_coord[x];
+            const uint32_t qx = kx & 0x7fffu;
+            const bool earlier = (kx >> 30) & 1u;
+            const uint32_t field = (kx >> 15) & 0x7fffu;
+            const uint32_t pull = earlier ? 0u : qx - field;
+            const uint32_t beg = cx ? s_cur[slot(cx - 1)] : 0u, end = s_cur[slot(cx)];
+            uint32_t rank = 0, sigma = earlier ? field : 0u;
+            for (uint32_t y = beg; y < end; ++y) {
+                const uint32_t ky = s_key[y];
+                const uint32_t qy = ky & 0x7fffu;
+                rank += qy < qx;
+                sigma += (ky >> 31) & (uint32_t)(qy >= pull && qy < qx);
+            }
+            float alpha = sw.lr;
+            if (sigma != 0) alpha = __fdiv_rn(sw.lr, (float)sigma);
+            s_prod[beg + rank] = __fmul_rn(alpha, s_val[x]);
+            if (rank == 0) {  // every touch of a coordinate fetched the same Theta; the earliest one folds
+                lo[j] = beg;
+                hi[j] = end;
+                coord[j] = cx;
+                theta[j] = s_theta[x];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t j = 0; j < PER_THREAD; ++j) {  // eq. 4, in time order
+            if (hi[j] <= lo[j]) continue;
+            float t_k = theta[j];
+            for (uint32_t m = lo[j]; m < hi[j]; ++m) t_k = __fsub_rn(t_k, s_prod[m]);
+            theta_of[i][coord[j]] = t_k;
+        }
+        __syncthreads();  // the next tile reuses the LDS arrays
     }
 }
 
@@ -763,7 +1000,19 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
                        reinterpret_cast<uint32_t *>(wsb + lay.bounds),
                        reinterpret_cast<uint32_t *>(wsb + lay.tile_tensor));
         CHECK_LAUNCH();
-        ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep, dim3((unsigned)lay.ntiles), dim3(BLOCK), s, sw);
+        // several tiles per workgroup once there are enough tiles to fill the chip many times over
+        uint32_t tpb = lay.ntiles >= 65536 ? 4u : 1u;
+        if (const char *e = std::getenv("ADACOMP_TPB")) tpb = (uint32_t)std::atoi(e);
+        if (tpb != 4 && tpb != 2) tpb = 1;
+        const dim3 grid((unsigned)((lay.ntiles + tpb - 1) / tpb));
+        const char *kind = std::getenv("ADACOMP_SWEEP_KERNEL");  // "long": the general kernel also for short queues
+        const bool short_queue = Q <= PASS_SHORT && !(kind && std::strcmp(kind, "long") == 0);
+        if (short_queue && tpb == 4) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_short<4>, grid, dim3(BLOCK), s, sw);
+        else if (short_queue && tpb == 2) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_short<2>, grid, dim3(BLOCK), s, sw);
+        else if (short_queue) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_short<1>, dim3((unsigned)lay.ntiles), dim3(BLOCK), s, sw);
+        else if (tpb == 4) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep<4>, grid, dim3(BLOCK), s, sw);
+        else if (tpb == 2) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep<2>, grid, dim3(BLOCK), s, sw);
+        else ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep<1>, dim3((unsigned)lay.ntiles), dim3(BLOCK), s, sw);
         CHECK_LAUNCH();
         ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP_SLOW, k_sweep_slow,
                        dim3((unsigned)std::min<uint64_t>(lay.ntiles, SLOW_GRID)), dim3(BLOCK), s, sw);

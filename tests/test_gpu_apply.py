@@ -500,3 +500,37 @@ def test_update_validate_and_malformed_entries_are_skipped(ac, dev, monkeypatch)
         monkeypatch.setenv("ADACOMP_APPLY_PLAN", plan)
         got, _, _ = run_gpu(ac, theta0, broken, pulls, 0.05, dev)
         assert compare(got, want, f"{plan}: out-of-range entry skipped") == 0
+
+
+@pytest.mark.parametrize("kernel,tpb", [("short", "1"), ("short", "2"), ("short", "4"), ("long", "1"), ("long", "2"), ("long", "4")])
+def test_sweep_kernels_and_tiles_per_workgroup(ac, dev, monkeypatch, kernel, tpb):
+    """The sweep has a kernel for queues of up to 32 updates (all loads of a workgroup's tiles
+    requested ahead) and a general one, each working through 1, 2 or 4 tiles per workgroup; forced
+    each way on queues with ragged tile counts, empty tiles, tiles that overflow into the fallback
+    kernel, zero-valued entries and pulls that reach back across calls: always the oracle's result."""
+    monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
+    monkeypatch.setenv("ADACOMP_TPB", tpb)
+    if kernel == "long":
+        monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", "long")
+    rng = np.random.default_rng(7 + int(tpb))
+    sizes = [2048 * 5 + 3, 1, 0, 2048 * 2, 70_001]            # 6 + 1 + 0 + 2 + 35 tiles of 2048
+    Q = 20
+    ups = random_updates(rng, sizes, Q, 0.004, zero_frac=0.1)
+    # a hot stretch: every update hits the same 40 parameters of one tile -> that tile overflows its stage
+    hot = np.arange(4100, 4140, dtype=np.uint32)
+    for q in range(Q):
+        off, idx, val = ups[q]
+        a, b = int(off[0]), int(off[1])
+        merged = np.union1d(idx[a:b], hot).astype(np.uint32)
+        v = rng.standard_normal(merged.size).astype(np.float32)
+        shift = merged.size - (b - a)
+        ups[q] = (np.concatenate([off[:1], off[1:] + shift]).astype(np.uint64),
+                  np.concatenate([merged, idx[b:]]), np.concatenate([v, val[b:]]))
+    pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    want = run_oracle(theta0, ups, pulls, 0.02)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev)
+    assert st.t == Q
+    assert compare(got, want, f"{kernel} kernel, {tpb} tiles per workgroup, one call") == 0
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev, chunks=[7, 1, 12], history=Q)
+    assert compare(got, want, f"{kernel} kernel, {tpb} tiles per workgroup, three calls with history") == 0
