@@ -234,3 +234,31 @@ def test_many_small_tensors_ties_and_unaligned(ac, dev):
         at += n + 1
     for rate in (0.003, 0.05, 0.5):
         check(ac, tensors, rate, what="many small")
+
+
+def test_small_tensor_with_clustered_large_values(ac, dev):
+    """One workgroup per tensor: all large entries sit in a stretch that belongs to one or two waves,
+    whose candidate slots in LDS overflow; the workgroup must then finish from the tensor itself."""
+    gen = torch.Generator(device=dev).manual_seed(31)
+    n = 200_003
+    g = torch.randn(n, generator=gen, device=dev) * 1e-3
+    g[60_001:60_001 + 3_000] = torch.randn(3_000, generator=gen, device=dev)
+    h = torch.randn(n, generator=gen, device=dev) * 1e-3
+    h[::4096] *= 1000.0
+    for rate in (0.01, 0.002, 0.0001):
+        check(ac, [g, h, g[1:70_000]], rate, what="small, clustered")
+
+
+def test_groups_of_tensors_reuse_the_candidate_regions(ac, dev, monkeypatch):
+    """With the region size forced down to 1 MB the 8 tensors of the mid-size configuration split into
+    several groups that reuse one set of candidate regions (a tensor larger than the limit forms a
+    group of its own); the selection must not change."""
+    g = workloads.gradient("cnn_select", 5, device=dev) + [workloads.gradient_layer("mid", 0, 2, 884736, dev),
+                                                           workloads.gradient_layer("mid", 0, 3, 663552, dev)]
+    want = [update_to_host(gpu_select(ac, g, r)) for r in (0.01, 0.002)]
+    for mb in ("1", "3", "0"):
+        monkeypatch.setenv("ADACOMP_SELECT_GROUP_MB", mb)
+        for r, w in zip((0.01, 0.002), want):
+            assert_update_equal(update_to_host(gpu_select(ac, g, r)), w, f"group size {mb} MB")
+    monkeypatch.delenv("ADACOMP_SELECT_GROUP_MB")
+    check(ac, g, 0.01, what="groups, default size")
