@@ -534,3 +534,29 @@ def test_sweep_kernels_and_tiles_per_workgroup(ac, dev, monkeypatch, kernel, tpb
     assert compare(got, want, f"{kernel} kernel, {tpb} tiles per workgroup, one call") == 0
     got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev, chunks=[7, 1, 12], history=Q)
     assert compare(got, want, f"{kernel} kernel, {tpb} tiles per workgroup, three calls with history") == 0
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_queues_shapes_and_call_splits(ac, dev, seed):
+    """Seeded random queues: tensor sizes from 0 to 300K, 2 to 60 updates of random density (so short
+    and long queues, large and one-parameter tiles), zero-valued entries, random pulls, applied in
+    one call and in random splits with a trace; the plan is whatever the library chooses."""
+    rng = np.random.default_rng(3000 + seed)
+    L = int(rng.integers(1, 7))
+    sizes = [int(rng.choice([0, 1, 5, 2048, 2049, int(rng.integers(1, 300_000)), int(rng.integers(1, 5_000))])) for _ in range(L)]
+    Q = int(rng.integers(2, 61))
+    density = float(rng.choice([0.0005, 0.004, 0.03, 0.3]))
+    ups = random_updates(rng, sizes, Q, density, zero_frac=float(rng.choice([0.0, 0.2])))
+    pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    want = run_oracle(theta0, ups, pulls, 0.01)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.01, dev)
+    assert st.t == Q
+    assert compare(got, want, f"random queue {seed}: Q={Q} density={density} sizes={sizes}") == 0
+    chunks, left = [], Q
+    while left:
+        c = int(rng.integers(1, left + 1))
+        chunks.append(c)
+        left -= c
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.01, dev, chunks=chunks, history=Q)
+    assert compare(got, want, f"random queue {seed} in calls of {chunks}") == 0

@@ -262,3 +262,29 @@ def test_groups_of_tensors_reuse_the_candidate_regions(ac, dev, monkeypatch):
             assert_update_equal(update_to_host(gpu_select(ac, g, r)), w, f"group size {mb} MB")
     monkeypatch.delenv("ADACOMP_SELECT_GROUP_MB")
     check(ac, g, 0.01, what="groups, default size")
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_rates_and_counts(ac, dev, seed):
+    """Seeded random mixes of tensor sizes (1 .. 600K, so both the one-workgroup path and the streaming
+    pipeline run in one call), value distributions, rates and per-tensor counts, including 0 and n."""
+    rng = np.random.default_rng(1000 + seed)
+    gen = torch.Generator(device=dev).manual_seed(2000 + seed)
+    L = int(rng.integers(1, 24))
+    sizes = [int(rng.choice([1, 2, 63, 64, 65, 255, 257, 4096, int(rng.integers(1, 600_000)), int(rng.integers(1, 40_000))]))
+             for _ in range(L)]
+    tensors = []
+    for n in sizes:
+        kind = int(rng.integers(0, 4))
+        x = torch.randn(n, generator=gen, device=dev)
+        if kind == 1:
+            x = (x * 3).round() / 3                      # few levels: ties everywhere
+        elif kind == 2:
+            x = x * (torch.rand(n, generator=gen, device=dev) < 0.1)      # 90 % zeros
+        elif kind == 3:
+            x = x.abs().pow(8.0) * 1e-20                 # wide dynamic range, denormals
+        tensors.append(x.contiguous())
+    rate = float(rng.choice([0.0003, 0.004, 0.03, 0.2, 0.7]))
+    check(ac, tensors, rate, what=f"random {seed}")
+    ks = [int(rng.choice([0, 1, n, n // 2, min(n, 7), int(rng.integers(0, n + 1))])) for n in sizes]
+    check(ac, tensors, rate, k_override=ks, what=f"random {seed}, counts given")
