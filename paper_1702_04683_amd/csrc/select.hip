@@ -730,6 +730,7 @@ __device__ __forceinline__ void small_find_bin(const uint32_t *s_hist, uint32_t 
 }
 
 constexpr uint32_t SCAND = 448;  // candidate slots per wave of k_small (16 waves: 56 KB of LDS)
+constexpr uint32_t SMALL_SAMPLE_MIN = 32768;  // smallest tensor k_small samples before reading it whole
 
 // Digit of `key` at a level of the descent, if the bits above the digit equal `prefix`.
 __device__ __forceinline__ bool small_digit(uint32_t key, uint32_t prefix, uint32_t pshift, uint32_t shift,
@@ -791,7 +792,8 @@ __device__ __forceinline__ void small_hist_global(const SmallDesc &d, bool vec, 
 // last read, every wave compacts the entries of its contiguous share that lie in the threshold
 // bin or above, in index order, into LDS; the two lower levels of the descent and the ordered
 // write work on those.  If the candidates do not fit LDS, the lower levels and the write read
-// the tensor again instead.
+// the tensor again instead.  Larger tensors are sampled first (like the streaming pipeline
+// does), which usually replaces the level-0 pass over the whole tensor by one over an eighth.
 __global__ __launch_bounds__(SBLOCK) void k_small(const SmallDesc *S, uint32_t *out_idx, uint32_t *out_val) {
     __shared__ uint32_t s_hist[BINS];
     __shared__ uint32_t s_cidx[SWAVES][SCAND];
@@ -799,27 +801,17 @@ __global__ __launch_bounds__(SBLOCK) void k_small(const SmallDesc *S, uint32_t *
     __shared__ uint32_t s_wave[SWAVES];
     __shared__ uint32_t s_cnt[SWAVES], s_gt[SWAVES], s_eq[SWAVES];
     __shared__ uint32_t s_res[2];
-    __shared__ uint32_t s_fail;
+    __shared__ uint32_t s_fail, s_ns;
     const SmallDesc d = S[blockIdx.x];
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wv = tid / WAVE;
     const bool vec = ((uintptr_t)d.g & 15u) == 0;
     const uint32_t nquads = (d.n + 3) / 4;
 
-    // level 0: bits 30..19 of the key
-    for (uint32_t i = tid; i < BINS; i += SBLOCK) s_hist[i] = 0;
-    if (tid == 0) s_fail = 0;
-    __syncthreads();
-    small_hist_global(d, vec, s_hist, 0u, 31u, 19u, BINS);
-    __syncthreads();
-    small_find_bin(s_hist, BINS, d.k, s_wave, s_res);
-    const uint32_t bin0 = s_res[0];
-    uint32_t prefix = bin0, k_rem = d.k - s_res[1];
-    const uint32_t ncand = s_res[1] + s_hist[bin0];  // entries in the threshold bin or above
-    __syncthreads();
-
-    bool in_lds = ncand <= SWAVES * SCAND;
-    if (in_lds) {
-        // ordered compaction of the candidates, wave by wave over contiguous shares
+    // Ordered compaction of the entries whose key lies in bin `bin_lo` (of level 0) or above, wave
+    // by wave over contiguous shares, into the waves' LDS slots.  False if a wave ran out of slots.
+    auto collect = [&](uint32_t bin_lo) -> bool {
+        if (tid == 0) s_fail = 0;
+        __syncthreads();
         const uint32_t share = (nquads + SWAVES - 1) / SWAVES;
         const uint32_t q_lo = wv * share, q_hi = q_lo + share < nquads ? q_lo + share : nquads;
         uint32_t filled = 0;
@@ -836,7 +828,7 @@ __global__ __launch_bounds__(SBLOCK) void k_small(const SmallDesc *S, uint32_t *
                 uint32_t before = 0, total = 0;  // candidates in lower lanes; in the whole piece
 #pragma unroll
                 for (uint32_t c = 0; c < 4; ++c) {
-                    take[c] = q < q_hi && q * 4 + c < d.n && (mag_key(bits[c]) >> 19) >= bin0;
+                    take[c] = q < q_hi && q * 4 + c < d.n && (mag_key(bits[c]) >> 19) >= bin_lo;
                     const uint64_t m = __ballot(take[c]);
                     before += lanes_below(m);
                     total += popc64(m);
@@ -862,7 +854,92 @@ __global__ __launch_bounds__(SBLOCK) void k_small(const SmallDesc *S, uint32_t *
             if (!ok) s_fail = 1;
         }
         __syncthreads();
-        in_lds = s_fail == 0;
+        return s_fail == 0;
+    };
+    // Histogram of one level of the descent over the candidates in LDS (s_hist zeroed by the caller).
+    auto hist_candidates = [&](uint32_t pre, uint32_t pshift, uint32_t shift, uint32_t nbins) {
+        uint32_t zeros = 0;
+        for (uint32_t e = lane; e < s_cnt[wv]; e += WAVE) {
+            uint32_t digit;
+            if (small_digit(mag_key(s_cval[wv][e]), pre, pshift, shift, nbins, digit)) {
+                if (digit == 0) ++zeros;
+                else atomicAdd(&s_hist[digit], 1u);
+            }
+        }
+        if (zeros) atomicAdd(&s_hist[0], zeros);
+    };
+
+    uint32_t prefix = 0, k_rem = d.k;
+    bool in_lds = false, level0_done = false;
+
+    // A tensor that is worth it is first sampled, one 1 KB piece in eight: from the sample a
+    // conservative bin is chosen, one read of the tensor collects everything in that bin or above,
+    // and if that is at least k entries (and fits LDS) the whole descent runs on them.
+    if (d.n >= SMALL_SAMPLE_MIN && 2 * d.k <= SWAVES * SCAND) {
+        for (uint32_t i = tid; i < BINS; i += SBLOCK) s_hist[i] = 0;
+        if (tid == 0) s_ns = 0;
+        __syncthreads();
+        const uint32_t npieces = (nquads + WAVE - 1) / WAVE;
+        uint32_t zeros = 0, mine = 0;
+        for (uint32_t j = wv; j * 8 < npieces; j += SWAVES) {
+            uint32_t p = j * 8 + ((j * 5u) & 7u);  // a different piece of every eight
+            if (p >= npieces) p = npieces - 1;
+            const uint32_t q = p * WAVE + lane;
+            if (q >= nquads) continue;
+            const uint4 v = load4(d.g, q * 4, d.n, vec);
+            const uint32_t bits[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (uint32_t c = 0; c < 4; ++c) {
+                if (q * 4 + c >= d.n) continue;
+                ++mine;
+                const uint32_t digit = mag_key(bits[c]) >> 19;
+                if (digit == 0) ++zeros;
+                else atomicAdd(&s_hist[digit], 1u);
+            }
+        }
+        if (zeros) atomicAdd(&s_hist[0], zeros);
+        if (mine) atomicAdd(&s_ns, mine);
+        __syncthreads();
+        const uint32_t ns = s_ns;
+        const float kf = (float)d.k * (float)ns / (float)d.n;
+        const uint32_t want = (uint32_t)ceilf(kf + 6.0f * sqrtf(kf) + 8.0f) + 1u;
+        if (want <= ns) {  // uniform
+            small_find_bin(s_hist, BINS, want, s_wave, s_res);
+            const uint32_t bin_lo = s_res[0];
+            __syncthreads();
+            if (bin_lo > 0 && collect(bin_lo)) {
+                uint32_t m = 0;
+                for (uint32_t w = 0; w < SWAVES; ++w) m += s_cnt[w];
+                if (m >= d.k) {  // the k largest are all among the candidates
+                    in_lds = true;
+                    for (uint32_t i = tid; i < BINS; i += SBLOCK) s_hist[i] = 0;
+                    __syncthreads();
+                    hist_candidates(0u, 31u, 19u, BINS);
+                    __syncthreads();
+                    small_find_bin(s_hist, BINS, d.k, s_wave, s_res);
+                    prefix = s_res[0];
+                    k_rem = d.k - s_res[1];
+                    level0_done = true;
+                    __syncthreads();
+                }
+            }
+        }
+    }
+
+    if (!level0_done) {
+        // level 0 from the whole tensor: bits 30..19 of the key
+        __syncthreads();
+        for (uint32_t i = tid; i < BINS; i += SBLOCK) s_hist[i] = 0;
+        __syncthreads();
+        small_hist_global(d, vec, s_hist, 0u, 31u, 19u, BINS);
+        __syncthreads();
+        small_find_bin(s_hist, BINS, d.k, s_wave, s_res);
+        const uint32_t bin0 = s_res[0];
+        prefix = bin0;
+        k_rem = d.k - s_res[1];
+        const uint32_t ncand = s_res[1] + s_hist[bin0];  // entries in the threshold bin or above
+        __syncthreads();
+        in_lds = ncand <= SWAVES * SCAND && collect(bin0);
     }
 
     // levels 1 and 2: bits 18..7 and 6..0, among the entries that share the prefix found so far
@@ -874,15 +951,7 @@ __global__ __launch_bounds__(SBLOCK) void k_small(const SmallDesc *S, uint32_t *
         for (uint32_t i = tid; i < nbins; i += SBLOCK) s_hist[i] = 0;
         __syncthreads();
         if (in_lds) {
-            uint32_t zeros = 0;
-            for (uint32_t e = lane; e < s_cnt[wv]; e += WAVE) {
-                uint32_t digit;
-                if (small_digit(mag_key(s_cval[wv][e]), prefix, pshift, shift, nbins, digit)) {
-                    if (digit == 0) ++zeros;
-                    else atomicAdd(&s_hist[digit], 1u);
-                }
-            }
-            if (zeros) atomicAdd(&s_hist[0], zeros);
+            hist_candidates(prefix, pshift, shift, nbins);
         } else {
             small_hist_global(d, vec, s_hist, prefix, pshift, shift, nbins);
         }
