@@ -23,7 +23,8 @@ namespace {
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t WAVES = BLOCK / WAVE;
 constexpr uint32_t SCAN_BLOCK = 1024;
-constexpr uint32_t SCAN_ITEMS = 4;   // consecutive counts per thread and round of the single-workgroup scan (16 was slower)
+constexpr uint32_t SCAN_ITEMS = 4;   // consecutive counts per thread and stretch of the single-workgroup scan
+constexpr uint32_t SCAN_SUB = 4;     // stretches per round
 constexpr uint32_t MAGIC = 0x31434441u;
 
 struct Wire {
@@ -83,25 +84,35 @@ __global__ __launch_bounds__(BLOCK) void k_wire_measure(Wire w, const uint32_t *
     }
 }
 
-// nw[0..B) -> exclusive prefix sums, nw[B] = sum.  One workgroup.
+// nw[0..B) -> exclusive prefix sums, nw[B] = sum.  One workgroup.  A round covers SCAN_SUB
+// stretches of SCAN_BLOCK * SCAN_ITEMS counts; their loads are issued together, so that the
+// memory latency is paid once per round and not once per stretch.
 __device__ __forceinline__ void scan_words(const Wire &w, uint32_t *s_wave) {
+    constexpr uint32_t STRETCH = SCAN_BLOCK * SCAN_ITEMS;
     uint32_t carry = 0;
-    for (uint32_t base = 0; base < w.B; base += SCAN_BLOCK * SCAN_ITEMS) {
-        const uint32_t i0 = base + threadIdx.x * SCAN_ITEMS;
-        uint32_t v[SCAN_ITEMS], sum = 0;
+    for (uint32_t base = 0; base < w.B; base += STRETCH * SCAN_SUB) {
+        uint32_t v[SCAN_SUB][SCAN_ITEMS];
 #pragma unroll
-        for (uint32_t j = 0; j < SCAN_ITEMS; ++j) {
-            v[j] = i0 + j < w.B ? w.nw[i0 + j] : 0u;
-            sum += v[j];
-        }
-        uint32_t all;
-        uint32_t run = carry + block_exclusive_scan<SCAN_BLOCK / WAVE>(sum, s_wave, all);
+        for (uint32_t u = 0; u < SCAN_SUB; ++u) {
+            const uint32_t i0 = base + u * STRETCH + threadIdx.x * SCAN_ITEMS;
 #pragma unroll
-        for (uint32_t j = 0; j < SCAN_ITEMS; ++j) {
-            if (i0 + j < w.B) w.nw[i0 + j] = run;
-            run += v[j];
+            for (uint32_t j = 0; j < SCAN_ITEMS; ++j) v[u][j] = i0 + j < w.B ? w.nw[i0 + j] : 0u;
         }
-        carry += all;
+#pragma unroll
+        for (uint32_t u = 0; u < SCAN_SUB; ++u) {
+            const uint32_t i0 = base + u * STRETCH + threadIdx.x * SCAN_ITEMS;
+            uint32_t sum = 0;
+#pragma unroll
+            for (uint32_t j = 0; j < SCAN_ITEMS; ++j) sum += v[u][j];
+            uint32_t all;
+            uint32_t run = carry + block_exclusive_scan<SCAN_BLOCK / WAVE>(sum, s_wave, all);
+#pragma unroll
+            for (uint32_t j = 0; j < SCAN_ITEMS; ++j) {
+                if (i0 + j < w.B) w.nw[i0 + j] = run;
+                run += v[u][j];
+            }
+            carry += all;
+        }
     }
     if (threadIdx.x == 0) w.nw[w.B] = carry;
 }
