@@ -38,8 +38,9 @@ def cpu_baseline(cfg, rate, lr, pulls, n_updates=16, layer=0):
 
     whole = cfg != "flat"
     layers = list(range(len(workloads.sizes_of(cfg)))) if whole else [layer]
-    if whole:
-        n_updates = len(pulls)
+    if whole:     # about 1.6e8 elements through the oracle: 10 to 20 s
+        n_updates = max(1, min(len(pulls), int(1.6e8 // sum(workloads.sizes_of(cfg)))))
+    print(f"[bench] cpu baseline: oracle on {n_updates} updates", file=sys.stderr, flush=True)
     grads = [[workloads.gradient_layer(cfg, q, l).numpy() for l in layers] for q in range(n_updates)]
     theta = [t.numpy().copy() for t in workloads.theta0(cfg, layers=layers)]
     ps = oracle.ParameterServer(theta)
@@ -66,9 +67,10 @@ def main():
                     help="one adacomp_select call per worker gradient instead of one call over all 16")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the 16 independent selects of a step are spread over (each has its own workspace)")
-    ap.add_argument("--workload", default="flat", choices=["flat", "paper_cnn"],
+    ap.add_argument("--workload", default="flat", choices=["flat", "paper_cnn", "cnn_apply", "mid"],
                     help="flat: the roofline configuration (default, the one the metric is quoted on); paper_cnn: the "
-                         "211,690-parameter network and 200 workers of the paper's experiments (latency regime)")
+                         "211,690-parameter network and 200 workers of the paper's experiments (latency regime); "
+                         "cnn_apply, mid: the small and the mid-size CNN configurations")
     ap.add_argument("--rate", type=float, default=None, help="compression ratio c (default: the workload's first)")
     ap.add_argument("--graph", action="store_true",
                     help="record one step in a HIP graph and time replays of it (the kernel timing for `roofline` then "
@@ -152,12 +154,19 @@ def main():
         selects()
         ac.adacomp_apply(params, state, queue, lr, app_ws)
 
-    if args.copy_calibration and not small:     # reads 4e9 bytes, writes 4e9 bytes
+    copy_ceiling = None
+    if args.copy_calibration and cfg == "flat":     # reads 4e9 bytes, writes 4e9 bytes
         src = torch.cat([g.view(-1) for g in grads[0]])
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
         torch.cuda.synchronize()
+        copy_ceiling = 5 * 2 * 4.0 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
         del src, dst
 
     for _ in range(args.warmup):
@@ -204,7 +213,7 @@ def main():
     achieved = alg_bytes / f_avg_s / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "filter_flat_traffic.json")
-    if os.path.exists(tpath) and not small:   # HBM bytes per step from the committed rocprofv3 --pmc summary
+    if os.path.exists(tpath) and cfg == "flat":   # HBM bytes per step from the committed rocprofv3 --pmc summary
         with open(tpath) as f:
             per_step = json.load(f).get("hbm_bytes_per_step")
         traffic = per_step / launches_per_step if per_step else None
@@ -216,10 +225,14 @@ def main():
         "config": {"workload": ("flat: 100 tensors x 10M fp32 = 1e9 elements per worker gradient, "
                                 "95% N(0,1e-5) + 5% N(0,1e-2), rate 0.5% per tensor, 16 queued updates, "
                                 "staleness U[1,16]; step = select of the 16 worker gradients + 1 apply of the queue")
-                   if not small else
+                   if cfg == "flat" else
                    (f"paper_cnn: 8 tensors, 211,690 fp32 parameters (Sec. 5.1), heavy-tailed gradients, rate {rate} per "
                     "tensor, 200 queued worker updates, staleness U[1,200]; step = select of the 200 worker gradients "
-                    "+ 1 apply of the queue (latency regime: microseconds of work per launch)"),
+                    "+ 1 apply of the queue (latency regime: microseconds of work per launch)")
+                   if small else
+                   (f"{cfg}: {L} tensors, {N} fp32 parameters, {c['dist']} gradients, rate {rate} per tensor, {Q} queued "
+                    f"worker updates, staleness U[1,{c['max_staleness']}]; step = select of the {Q} worker gradients + "
+                    "1 apply of the queue"),
                    "select_calls_per_step": 1 if batched else Q, "select_streams": ns, "hip_graph": bool(args.graph),
                    "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q},
         "roofline": {"bound": "hbm", "kernel": "k_small" if small else "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
@@ -248,6 +261,8 @@ def main():
     out["apply_entries_per_s"] = Q * cap / (app_ms * 1e-3)
     if kernels:
         out["kernels"] = kernels
+    if copy_ceiling is not None:   # what a plain device copy of 4 GB reaches on this machine (read + write bytes per second)
+        out["copy_ceiling_GBps"] = copy_ceiling
 
     if args.wire:      # one worker update (100 tensors x 50,000 entries) through the wire format and back
         u = updates[0]

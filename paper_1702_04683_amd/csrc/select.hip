@@ -694,10 +694,17 @@ __global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L, uint
             pidx[off[i] + lane] = rc[i].x;
             pval[off[i] + lane] = rc[i].y;
         }
-        for (uint32_t e = WAVE + lane; e < cnt[i]; e += WAVE) {  // fuller segments
-            const uint2 c = cand[(uint64_t)i * d.cap + e];
-            pidx[off[i] + e] = c.x;
-            pval[off[i] + e] = c.y;
+        for (uint32_t e = WAVE + lane; e < cnt[i]; e += 2 * WAVE) {  // fuller segments: two loads in flight
+            uint2 c0, c1;
+            const bool second = e + WAVE < cnt[i];
+            c0 = cand[(uint64_t)i * d.cap + e];
+            if (second) c1 = cand[(uint64_t)i * d.cap + e + WAVE];
+            pidx[off[i] + e] = c0.x;
+            pval[off[i] + e] = c0.y;
+            if (second) {
+                pidx[off[i] + e + WAVE] = c1.x;
+                pval[off[i] + e + WAVE] = c1.y;
+            }
         }
     }
 }
