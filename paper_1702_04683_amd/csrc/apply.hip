@@ -46,7 +46,7 @@ constexpr uint32_t TILE_MAX = 2048;    // sweep plan: most coordinates per tile 
 constexpr uint32_t STAGE_CAP = 512;    // sweep plan: entries of the whole queue a tile can hold in LDS
 constexpr uint32_t SLOW_GRID = 1024;
 constexpr uint32_t PASS = 256;           // sweep plan: updates whose slices are staged together
-constexpr uint32_t PASS_SHORT = 32;      // sweep plan: longest queue the kernel for short queues takes
+constexpr uint32_t PASS_SHORT = 64;      // sweep plan: longest queue the kernel for short queues takes (one lane of wave 0 per update)
 // one launch costs about as much as this many bytes of memory traffic (4 us at 5 TB/s)
 constexpr double LAUNCH_COST_BYTES = 20e6;
 static_assert((TILE_MAX & (TILE_MAX - 1)) == 0 && TILE_MAX >= BLOCK && STAGE_CAP % BLOCK == 0 && STAGE_CAP <= 65535,
@@ -526,6 +526,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_short(Sweep sw) {
     __shared__ const float *s_valp[QS];
     __shared__ const uint32_t *s_pre[QS];
     __shared__ uint32_t s_tag[QS];
+    static_assert(QS == WAVE, "wave 0 serves one update per lane");
     __shared__ uint32_t s_off[TPB][QS + 1];  // per tile: staged position of the first entry of update q; [Q..QS] = entries
     __shared__ uint32_t s_b0[TPB][QS];
     __shared__ uint32_t s_wave[WAVES];
@@ -564,7 +565,8 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_short(Sweep sw) {
                 const uint32_t y = __shfl_up(incl, d);
                 if (tid >= (uint32_t)d) incl += y;
             }
-            if (tid <= QS) s_off[i][tid] = incl - len;  // lanes Q .. QS hold the total
+            s_off[i][tid] = incl - len;  // lanes at or beyond Q hold the total
+            if (tid == WAVE - 1) s_off[i][QS] = incl;
             if (mine) s_b0[i][tid] = row[i];
         }
     }

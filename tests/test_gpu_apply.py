@@ -504,7 +504,7 @@ def test_update_validate_and_malformed_entries_are_skipped(ac, dev, monkeypatch)
 
 @pytest.mark.parametrize("kernel,tpb", [("short", "1"), ("short", "2"), ("short", "4"), ("long", "1"), ("long", "2"), ("long", "4")])
 def test_sweep_kernels_and_tiles_per_workgroup(ac, dev, monkeypatch, kernel, tpb):
-    """The sweep has a kernel for queues of up to 32 updates (all loads of a workgroup's tiles
+    """The sweep has a kernel for queues of up to 64 updates (all loads of a workgroup's tiles
     requested ahead) and a general one, each working through 1, 2 or 4 tiles per workgroup; forced
     each way on queues with ragged tile counts, empty tiles, tiles that overflow into the fallback
     kernel, zero-valued entries and pulls that reach back across calls: always the oracle's result."""
