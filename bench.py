@@ -18,6 +18,7 @@ pass), timed live with HIP events on the launch stream inside the timed steps;
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -212,11 +213,11 @@ def main():
     alg_bytes = Q * (4.0 * N + 8.0 * cap) / launches_per_step
     achieved = alg_bytes / f_avg_s / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "filter_flat_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_flat.md")
     if os.path.exists(tpath) and cfg == "flat":   # HBM bytes per step from the committed rocprofv3 --pmc summary
         with open(tpath) as f:
-            per_step = json.load(f).get("hbm_bytes_per_step")
-        traffic = per_step / launches_per_step if per_step else None
+            m = re.search(r"k_filter HBM bytes per step:\s*(\d+)", f.read())
+        traffic = float(m.group(1)) / launches_per_step if m else None
     out = {
         "metric": "gradient elements/sec compressed+applied",
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
