@@ -791,7 +791,7 @@ void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_updat
     uint64_t oldest = t0;
     for (uint32_t q = 0; q < Q; ++q) {
         entries += (double)updates[q].layer_off[L];
-        fits32 = fits32 && updates[q].layer_off[L] <= 0xffffffffull;
+        fits32 = fits32 && updates[q].layer_off[L] <= 0xffff0000ull;  // 32-bit entry numbers, with room for the loops' strides
         if (updates[q].pull_ts < oldest && updates[q].layer_off[L] > 0) oldest = updates[q].pull_ts;
     }
     lay.n_hist = (uint32_t)(t0 - oldest);

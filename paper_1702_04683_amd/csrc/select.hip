@@ -382,8 +382,9 @@ __device__ __forceinline__ void visit_range(const Source &src, uint32_t lo, uint
             }
         }
     }
-    // the rest: an unaligned source, or the ragged end of the range
-    for (; r < hi; r += PIECE) {
+    // the rest: an unaligned source, or the ragged end of the range (hi may be 2^32 - 1: the
+    // position is advanced only while it stays below hi, it must not wrap)
+    for (; r < hi; r = hi - r > PIECE ? r + PIECE : hi) {
         const uint32_t first = r + lane * 4;
         const uint4 v = load4<STREAM>(vals, first, hi, src.vec);
         uint32_t idx[4] = {first, first + 1, first + 2, first + 3};
@@ -1292,8 +1293,8 @@ __global__ __launch_bounds__(BLOCK) void k_identity(Workspace ws, uint32_t L, ui
     const uint32_t lo = (blockIdx.x - d.iblk_base) * IDENT_TILE;
     const uint32_t hi = d.n - lo < IDENT_TILE ? d.n : lo + IDENT_TILE;
     const uint32_t *g = reinterpret_cast<const uint32_t *>(d.g);
-    for (uint32_t i = lo + threadIdx.x; i < hi; i += BLOCK) {
-        out_idx[d.out_off + i] = i;
+    for (uint64_t i = (uint64_t)lo + threadIdx.x; i < hi; i += BLOCK) {  // 64-bit: hi may be 2^32 - 1
+        out_idx[d.out_off + i] = (uint32_t)i;
         out_val[d.out_off + i] = g[i];
     }
 }
