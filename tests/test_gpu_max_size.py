@@ -147,3 +147,48 @@ def test_apply_on_a_tensor_of_2_to_the_32_minus_1_parameters(monkeypatch):
         after = [int(theta[a:a + step].view(torch.int32).to(torch.int64).sum()) for a in range(0, N, step)]
         assert after == checksum_before, plan
         del st, ws, us
+
+
+def test_twenty_thousand_tensors(monkeypatch):
+    """Many tensors in one call (descriptor tables of megabytes, one workgroup or more per tensor in every
+    kernel): select through the one-workgroup path and through the streaming pipeline, then apply."""
+    import paper_1702_04683_amd as ac
+    from helpers import assert_update_equal, update_to_host
+    ac.load_library()
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(47)
+    L = 20_000
+    sizes = rng.integers(0, 300, size=L).tolist()
+    sizes[5], sizes[L - 1] = 9000, 70_000
+    flat = torch.randn(sum(sizes) + L, generator=torch.Generator(device=dev).manual_seed(3), device=dev)
+    tensors, at = [], 0
+    for n in sizes:
+        tensors.append(flat[at:at + n])
+        at += n + 1                                       # most tensors start off a 16-byte boundary
+    host = [t.cpu().numpy() for t in tensors]
+    want = oracle.select(host, 0.05)
+    print("[many tensors] select, one workgroup per tensor", flush=True)
+    u = gpu_select(ac, tensors, 0.05)
+    assert_update_equal(update_to_host(u), want, "20000 tensors")
+    print("[many tensors] select, streaming pipeline", flush=True)
+    monkeypatch.setenv("ADACOMP_SELECT_SMALL", "0")
+    assert_update_equal(update_to_host(gpu_select(ac, tensors, 0.05)), want, "20000 tensors, pipeline")
+    monkeypatch.delenv("ADACOMP_SELECT_SMALL")
+    print("[many tensors] apply", flush=True)
+    theta_host = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    ref = [t.copy() for t in theta_host]
+    ps = oracle.ParameterServer(ref)
+    ups = []
+    for q in range(3):
+        g = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+        off, idx, val = oracle.select(g, 0.05)
+        ps.apply(off, idx, val, 0, 0.1)
+        ups.append(ac.Update.from_host(off, idx, val, dev, pull_ts=0))
+    theta = [torch.from_numpy(t).to(dev) for t in theta_host]
+    st = ac.State(theta)
+    ws = torch.empty(max(256, ac.adacomp_apply_workspace(sizes, ups, st)), dtype=torch.uint8, device=dev)
+    ac.adacomp_apply(theta, st, ups, 0.1, ws)
+    torch.cuda.synchronize()
+    for l in range(L):
+        if sizes[l]:
+            assert np.array_equal(theta[l].cpu().numpy().view(np.uint32), ref[l].view(np.uint32)), f"tensor {l}"
