@@ -192,3 +192,39 @@ def test_twenty_thousand_tensors(monkeypatch):
     for l in range(L):
         if sizes[l]:
             assert np.array_equal(theta[l].cpu().numpy().view(np.uint32), ref[l].view(np.uint32)), f"tensor {l}"
+
+
+def test_keep_all_update_of_the_largest_tensor_applied_three_times():
+    """An update with 2^32 - 1 entries (every parameter, rate 1) goes through the update-by-update plan
+    with 64-bit entry numbers.  Applied three times with all pulls at time 0 the third application
+    sees every parameter changed twice: theta - lr g - lr g - (lr / 2) g, each step rounded as eqs. 4-5
+    say (keep-all selection = dense staleness-aware ASGD); torch evaluates that on the device."""
+    import paper_1702_04683_amd as ac
+    ac.load_library()
+    dev = torch.device("cuda:0")
+    step = 1 << 28
+    g = torch.empty(N, dtype=torch.float32, device=dev)
+    theta = torch.empty(N, dtype=torch.float32, device=dev)
+    gen = torch.Generator(device=dev).manual_seed(13)
+    for a in range(0, N, step):
+        g[a:a + step].normal_(0.0, 1e-2, generator=gen)
+        theta[a:a + step].normal_(0.0, 0.05, generator=gen)
+    g[12345] = 0.0                                        # one exact zero: it never counts in eq. 3
+    want = theta.clone()
+    lr = 0.1
+    for alpha in (lr, lr, np.float32(lr) / np.float32(2.0)):
+        for a in range(0, N, step):
+            want[a:a + step] -= g[a:a + step] * float(alpha)
+    want[12345] = theta[12345]
+    print("[max size] keep-all select", flush=True)
+    u = gpu_select(ac, [g], 1.0)
+    del g
+    ups = [u.view(0, 1, pull_ts=0) for _ in range(3)]
+    st = ac.State([theta])
+    ws = torch.empty(max(256, ac.adacomp_apply_workspace([N], ups, st)), dtype=torch.uint8, device=dev)
+    print(f"[max size] apply three times, workspace {ws.numel() / 1e9:.1f} GB", flush=True)
+    ac.adacomp_apply([theta], st, ups, lr, ws)
+    torch.cuda.synchronize()
+    assert st.t == 3
+    for a in range(0, N, step):
+        assert torch.equal(theta[a:a + step].view(torch.int32), want[a:a + step].view(torch.int32)), f"piece at {a}"
