@@ -288,3 +288,19 @@ def test_random_shapes_rates_and_counts(ac, dev, seed):
     check(ac, tensors, rate, what=f"random {seed}")
     ks = [int(rng.choice([0, 1, n, n // 2, min(n, 7), int(rng.integers(0, n + 1))])) for n in sizes]
     check(ac, tensors, rate, k_override=ks, what=f"random {seed}, counts given")
+
+
+@pytest.mark.parametrize("small", ["0", "1"])
+def test_sizes_around_every_internal_boundary(ac, dev, monkeypatch, small):
+    """Tensor sizes at and next to the sizes the kernels are built around (4-element loads, 256-element
+    pieces, 8192-element wave segments, 2048-candidate chunks, the 2^18 limit of the one-workgroup
+    path), each with k = 1, k = n - 1 and two rates, through the pipeline and through the one-workgroup path."""
+    monkeypatch.setenv("ADACOMP_SELECT_SMALL", small)
+    gen = torch.Generator(device=dev).manual_seed(77)
+    sizes = [1, 2, 3, 4, 5, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049, 8191, 8192, 8193, 16383, 16384, 16385,
+             65535, 65537, 262143, 262144, 262145, 262144 + 8192, 524287, 524288, 524289]
+    tensors = [(torch.randn(n, generator=gen, device=dev) * 7).round() / 7 for n in sizes]    # ties are common
+    for rate in (0.01, 0.2):
+        check(ac, tensors, rate, what=f"boundary sizes, small={small}")
+    check(ac, tensors, 0.5, k_override=[1] * len(sizes), what="boundary sizes, k = 1")
+    check(ac, tensors, 0.5, k_override=[max(n - 1, 0) for n in sizes], what="boundary sizes, k = n - 1")
