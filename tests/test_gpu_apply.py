@@ -560,3 +560,25 @@ def test_random_queues_shapes_and_call_splits(ac, dev, seed):
         left -= c
     got, _, st = run_gpu(ac, theta0, ups, pulls, 0.01, dev, chunks=chunks, history=Q)
     assert compare(got, want, f"random queue {seed} in calls of {chunks}") == 0
+
+
+def test_calls_longer_than_the_trace(ac, dev):
+    """A call that applies more updates than the trace can remember keeps the last `d` of them; the
+    next call may reach back exactly that far and no further."""
+    rng = np.random.default_rng(35)
+    sizes, d = [3000, 9], 4
+    Q = 10 + 3 + 12 + 1
+    ups = random_updates(rng, sizes, Q, 0.05, zero_frac=0.1)
+    call_start = [0] * 10 + [10] * 3 + [13] * 12 + [25]
+    pulls = [int(rng.integers(max(0, call_start[q] - d), q + 1)) for q in range(Q)]
+    pulls[10] = 10 - d                                   # the oldest remembered update, exactly
+    pulls[25] = 25 - d
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.05, dev, chunks=[10, 3, 12, 1], history=d)
+    want = run_oracle(theta0, ups, pulls, 0.05)
+    assert st.t == Q
+    assert compare(got, want, "calls longer than the trace") == 0
+    u = ac.Update.from_host(*ups[0], dev, pull_ts=Q - d - 1)
+    with pytest.raises(ac.AdaCompError) as e:
+        ac.adacomp_apply_workspace(sizes, [u], st)
+    assert e.value.code == -9
