@@ -304,3 +304,16 @@ def test_sizes_around_every_internal_boundary(ac, dev, monkeypatch, small):
         check(ac, tensors, rate, what=f"boundary sizes, small={small}")
     check(ac, tensors, 0.5, k_override=[1] * len(sizes), what="boundary sizes, k = 1")
     check(ac, tensors, 0.5, k_override=[max(n - 1, 0) for n in sizes], what="boundary sizes, k = n - 1")
+
+
+def test_counts_around_the_switch_between_filter_and_direct_descent(ac, dev):
+    """k just below, at and above n / 8 (above it the descent reads the tensor directly), a quarter, all
+    but one; on Gaussian data, on a tensor of NaNs with different payloads, and on one of infinities."""
+    gen = torch.Generator(device=dev).manual_seed(91)
+    n = 1_000_003
+    x = torch.randn(n, generator=gen, device=dev)
+    payload = torch.randint(0, 1 << 22, (n,), generator=gen, device=dev, dtype=torch.int32)
+    nans = (payload | 0x7FC00000 | (torch.randint(0, 2, (n,), generator=gen, device=dev, dtype=torch.int32) << 31)).view(torch.float32)
+    infs = torch.where(torch.rand(n, generator=gen, device=dev) < 0.5, float("inf"), float("-inf")).to(torch.float32)
+    for k in (n // 8 - 1, n // 8, n // 8 + 1, n // 4, n - 1, 3):
+        check(ac, [x, nans.contiguous(), infs.contiguous()], 0.5, k_override=[k, k, k], what=f"k = {k}")
