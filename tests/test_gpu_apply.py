@@ -582,3 +582,25 @@ def test_calls_longer_than_the_trace(ac, dev):
     with pytest.raises(ac.AdaCompError) as e:
         ac.adacomp_apply_workspace(sizes, [u], st)
     assert e.value.code == -9
+
+
+def test_queue_longer_than_the_sweep_can_number(ac, dev):
+    """More than 32767 updates in one call: the sweep's 15-bit update numbers do not suffice, the call
+    runs update by update (two launches each); staleness up to 50."""
+    rng = np.random.default_rng(36)
+    sizes = [40, 3]
+    Q = 33_000
+    ups = []
+    for q in range(Q):
+        i0 = np.unique(rng.integers(0, 40, 3)).astype(np.uint32)
+        i1 = np.array([int(rng.integers(0, 3))], dtype=np.uint32)
+        v = rng.standard_normal(i0.size + 1).astype(np.float32)
+        ups.append((np.array([0, i0.size, i0.size + 1], dtype=np.uint64), np.concatenate([i0, i1]), v))
+    pulls = [max(0, q - int(rng.integers(0, 51))) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    print("[apply] 33000 updates: gpu", flush=True)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 1e-3, dev)
+    assert st.t == Q
+    print("[apply] 33000 updates: oracle", flush=True)
+    want = run_oracle(theta0, ups, pulls, 1e-3)
+    assert compare(got, want, "33000 updates") == 0
