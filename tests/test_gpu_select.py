@@ -317,3 +317,21 @@ def test_counts_around_the_switch_between_filter_and_direct_descent(ac, dev):
     infs = torch.where(torch.rand(n, generator=gen, device=dev) < 0.5, float("inf"), float("-inf")).to(torch.float32)
     for k in (n // 8 - 1, n // 8, n // 8 + 1, n // 4, n - 1, 3):
         check(ac, [x, nans.contiguous(), infs.contiguous()], 0.5, k_override=[k, k, k], what=f"k = {k}")
+
+
+def test_two_streams_at_once(ac, dev):
+    """The library keeps no state between calls: two selects enqueued on two streams, each with its own
+    workspace and outputs, run side by side and both give the oracle's result."""
+    g = [workloads.gradient("cnn_select", 7, device=dev), workloads.gradient("cnn_select", 8, device=dev)]
+    sizes = [t.numel() for t in g[0]]
+    streams = [torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)]
+    cap = sum(ac.adacomp_count(n, 0.01) for n in sizes)
+    outs = [ac.Update(len(sizes), cap, dev) for _ in range(2)]
+    wss = [torch.empty(ac.adacomp_select_workspace(sizes, 0.01), dtype=torch.uint8, device=dev) for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for i in range(2):
+            ac.adacomp_select(g[i], 0.01, outs[i], wss[i], stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert_update_equal(update_to_host(outs[i]), oracle.select(host(g[i]), 0.01), f"stream {i}")
