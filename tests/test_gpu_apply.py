@@ -182,20 +182,24 @@ def test_cnn_apply_config(ac, dev):
         assert np.all(np.abs(a - b) <= 3 * Q * 2.0 ** -24 * np.maximum(np.abs(b), 0.2))
 
 
-def test_mid_apply_config(ac, dev):
-    """Config 'mid-size CNN' at 1%: 64 queued updates, staleness uniform in [1, 64].  The six
-    tensors below 1M entries are checked in full against the oracle; the updates come from
-    the oracle's own selection."""
-    cfg, rate = "mid", 0.01
+@pytest.mark.parametrize("rate", [0.001, 0.01, 0.1])
+def test_mid_apply_config(ac, dev, rate):
+    """Config 'mid-size CNN' at 0.1%, 1% and 10% (at 10% every parameter is touched 6 times on
+    average: tiles of a few dozen parameters): 64 queued updates, staleness uniform in [1, 64].
+    The six tensors below 1M entries are checked in full against the oracle; the updates come
+    from the oracle's own selection."""
+    cfg = "mid"
     layers = [0, 1, 2, 3, 4, 7]
     Q, lr = 64, workloads.CONFIGS[cfg]["lr"]
     pulls = workloads.pull_timestamps(workloads.staleness(cfg))
     grads = [[x.numpy() for x in workloads.gradient(cfg, q, layers=layers)] for q in range(Q)]
     ups = oracle_select_parallel(grads, rate, threads=12)
     theta0 = [t.numpy() for t in workloads.theta0(cfg, layers=layers)]
+    print(f"[apply] mid at {rate}: gpu", flush=True)
     got, _, _ = run_gpu(ac, theta0, ups, pulls, lr, dev)
-    want = run_oracle(theta0, ups, pulls, lr)
-    assert compare(got, want, "mid apply") == 0
+    print(f"[apply] mid at {rate}: oracle", flush=True)
+    want = run_oracle(theta0, ups, pulls, lr, method=oracle.HISTORY_BITMAP if rate > 0.05 else oracle.HISTORY_LISTS)
+    assert compare(got, want, f"mid apply at {rate}") == 0
 
 
 def test_extreme_staleness_long_queue(ac, dev):
