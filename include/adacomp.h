@@ -185,7 +185,8 @@ int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_state_t
  *            update pulled before this call has the earlier part of its window
  *            searched in the remembered updates' sorted index lists, by bisection, as
  *            Sec. 4 "Complexity" describes; with history_cap = 0 every pull_ts must be
- *            >= st->t
+ *            >= st->t; an update without entries has no staleness to look up and may
+ *            carry any pull_ts that is not in the future
  *   lr       alpha, finite
  *   workspace DEVICE, 256-byte aligned, >= adacomp_apply_workspace() bytes
  * The queue is executed either update by update (scatter) or in one sweep over

@@ -776,7 +776,8 @@ int check_pulls(const adacomp_state_t *st, const adacomp_update_t *updates, uint
     }
     for (uint32_t q = 0; q < Q; ++q) {
         if (updates[q].pull_ts > t0 + q) return ADACOMP_ERR_FUTURE_PULL;
-        if (updates[q].pull_ts + remembered < t0) return ADACOMP_ERR_HISTORY;
+        const bool empty = updates[q].layer_off[updates[q].num_layers] == 0;  // no entry, no staleness to look up
+        if (!empty && updates[q].pull_ts + remembered < t0) return ADACOMP_ERR_HISTORY;
     }
     return ADACOMP_OK;
 }

@@ -131,6 +131,9 @@ def test_apply_argument_checks_run_before_any_launch(lib):
     assert lib.adacomp_apply_workspace(n, 1, C.byref(st), upd, 1, C.byref(need)) == 0 and need.value >= 12
     upd[0].pull_ts = 3                                      # two timestamps back, nothing remembered
     assert lib.adacomp_apply_workspace(n, 1, C.byref(st), upd, 1, C.byref(need)) == -9
+    off[1], upd[0].cap = 0, 0                               # ... which an update without entries never needs
+    assert lib.adacomp_apply_workspace(n, 1, C.byref(st), upd, 1, C.byref(need)) == 0
+    off[1], upd[0].cap = 3, 3
     ring = (binding._Update * 4)()
     ring_off = (C.c_uint64 * 8)()
     st.history_cap, st.history_len = 4, 1

@@ -608,3 +608,39 @@ def test_queue_longer_than_the_sweep_can_number(ac, dev):
     print("[apply] 33000 updates: oracle", flush=True)
     want = run_oracle(theta0, ups, pulls, 1e-3)
     assert compare(got, want, "33000 updates") == 0
+
+
+def test_degenerate_calls(ac, dev):
+    """No tensors, no updates, empty updates only, tensors of zero size only: legal, nothing but the
+    timestamp changes."""
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+    none = ac.Update(0, 0, dev)
+    ac.adacomp_select([], 0.5, none, ws)
+    assert none.offsets == [0]
+    st = ac.State([])
+    ac.adacomp_apply([], st, [none, none], 0.1, ws)          # two pushes to a model without parameters
+    assert st.t == 2
+    ac.adacomp_apply([], st, [], 0.1, ws)
+    assert st.t == 2
+    theta = [torch.arange(10, dtype=torch.float32, device=dev), torch.empty(0, device=dev)]
+    before = theta[0].clone()
+    st = ac.State(theta)
+    empty = ac.Update.from_host(np.zeros(3, dtype=np.uint64), np.empty(0, np.uint32), np.empty(0, np.float32), dev)
+    for plan_q in (1, 5):
+        ac.adacomp_apply(theta, st, [empty] * plan_q, 0.1, ws)
+    torch.cuda.synchronize()
+    assert st.t == 6 and torch.equal(theta[0], before)
+    # empty updates carry pull_ts 0 throughout: without entries there is no staleness to look up;
+    # a fresh update after the six empty pushes takes the full step
+    u = ac.Update.from_host(np.array([0, 2, 2], dtype=np.uint64), np.array([1, 9], dtype=np.uint32),
+                            np.array([1.0, -1.0], dtype=np.float32), dev, pull_ts=6)
+    ac.adacomp_apply(theta, st, [u], 0.5, ws)
+    torch.cuda.synchronize()
+    assert theta[0].tolist() == [0.0, 0.5, 2.0, 3.0, 4.0, 5.0, 6.0, 7.0, 8.0, 9.5]
+    zero_size = [torch.empty(0, device=dev), torch.empty(0, device=dev)]
+    out = ac.Update(2, 0, dev)
+    ac.adacomp_select(zero_size, 0.3, out, ws)
+    st0 = ac.State(zero_size)
+    ac.adacomp_apply(zero_size, st0, [out], 0.1, ws)
+    torch.cuda.synchronize()
+    assert out.offsets == [0, 0, 0] and st0.t == 1
