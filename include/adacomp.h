@@ -27,6 +27,7 @@
  *     give identical results and exist for tests and measurements:
  *       ADACOMP_APPLY_PLAN=scatter|sweep   force one plan of adacomp_apply
  *       ADACOMP_SWEEP_KERNEL=long          sweep plan: the general kernel also for queues of <= 64 updates
+ *       ADACOMP_SWEEP_KERNEL=dense|tiled   sweep plan: always / never the kernel for dense queues (<= 256 updates)
  *       ADACOMP_TPB=1|2|4                  sweep plan: tiles per workgroup
  *       ADACOMP_SELECT_SMALL=0             small tensors take the streaming pipeline too
  *       ADACOMP_SELECT_GROUP_MB=<n>        candidate-region size per group of tensors (0: one group)

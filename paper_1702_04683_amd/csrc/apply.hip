@@ -47,6 +47,10 @@ constexpr uint32_t STAGE_CAP = 512;    // sweep plan: entries of the whole queue
 constexpr uint32_t SLOW_GRID = 1024;
 constexpr uint32_t PASS = 256;           // sweep plan: updates whose slices are staged together
 constexpr uint32_t PASS_SHORT = 64;      // sweep plan: longest queue the kernel for short queues takes (one lane of wave 0 per update)
+constexpr uint32_t DENSE_QMAX = 256;     // sweep plan: longest queue the kernel for dense queues takes
+// ... and the queued entries per parameter from which it is used, for queues of up to 64 updates
+// and for longer ones (measured crossovers against the sorting kernels: 0.5-1.0 and 1.4-1.8)
+constexpr double DENSE_PER_COORD = 1.0, DENSE_PER_COORD_LONG = 1.75;
 // one launch costs about as much as this many bytes of memory traffic (4 us at 5 TB/s)
 constexpr double LAUNCH_COST_BYTES = 20e6;
 static_assert((TILE_MAX & (TILE_MAX - 1)) == 0 && TILE_MAX >= BLOCK && STAGE_CAP % BLOCK == 0 && STAGE_CAP <= 65535,
@@ -704,6 +708,152 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_short(Sweep sw) {
     }
 }
 
+// The sweep for dense queues (about one queued entry per parameter or more).  There the lists
+// of a coordinate need no sorting: a tile is DTILE consecutive coordinates, thread c owns
+// coordinate c with Theta_c in a register, and the queue passes through LDS DQ updates at a
+// time as a dense [update][coordinate] array of values plus one presence word per coordinate.
+// The owner replays its touches in time order.  Its non-zero touches so far are one bit per
+// update in Z, so eq. 3 for a touch by update q pulled at j is a population count of Z over
+// the bits j .. q-1 (plus what the update had accumulated before the call).  alpha / sigma
+// comes from a table built with the same correctly rounded divide as everywhere else.
+// Queues of at most 64 * NW updates.  A slice of a sorted list inside a tile has at most DTILE
+// entries; what a malformed list adds beyond that, or outside the tile, is skipped.
+constexpr uint32_t DTILE = BLOCK;
+constexpr uint32_t DTILE_SHIFT = 8;
+static_assert(DTILE == 1u << DTILE_SHIFT, "dense sweep: one thread per coordinate of a tile");
+
+typedef const __attribute__((address_space(1))) uint32_t *global_u32;
+typedef const __attribute__((address_space(1))) float *global_f32;
+
+template <uint32_t NW, uint32_t DQ, bool PRE>
+__global__ __launch_bounds__(BLOCK) void k_sweep_dense(Sweep sw) {
+    constexpr uint32_t QMAX = 64 * NW;
+    constexpr uint32_t PER_WAVE = DQ / WAVES;
+    static_assert(DQ <= 32 && DQ % WAVES == 0 && QMAX <= BLOCK, "presence bits fit a word; thread q serves update q");
+    __shared__ float s_v[DQ][DTILE];
+    __shared__ uint32_t s_pr[PRE ? DQ : 1][DTILE];
+    __shared__ uint32_t s_p[DTILE];
+    __shared__ const uint32_t *s_idx[QMAX];
+    __shared__ const float *s_valp[QMAX];
+    __shared__ const uint32_t *s_pre[QMAX];
+    __shared__ uint32_t s_b0[QMAX], s_len[QMAX], s_pull[QMAX];
+    __shared__ float s_alpha[QMAX];
+
+    const uint32_t tid = threadIdx.x, t = blockIdx.x;
+    const uint32_t lane = tid & (WAVE - 1);
+    const uint32_t wv = __builtin_amdgcn_readfirstlane(tid / WAVE);
+    const ParamDesc pd = sw.P[sw.tile_tensor[t]];
+    const uint32_t c0 = (t - (uint32_t)pd.tile_base) << DTILE_SHIFT;
+    const uint32_t ncoord = pd.n - c0 < DTILE ? (uint32_t)(pd.n - c0) : DTILE;
+    float th = 0.f;
+    if (tid < ncoord) th = pd.theta[c0 + tid];
+    if (tid < sw.Q) {
+        const uint32_t *row = sw.B + (uint64_t)tid * (sw.ntiles + 1) + t;
+        const uint32_t b0 = row[0], b1 = row[1];
+        const UpdDesc u = sw.U[tid];
+        s_b0[tid] = b0;
+        const uint32_t len = b1 >= b0 ? b1 - b0 : 0u;  // bounds of an unsorted (malformed) list may cross
+        s_len[tid] = len < DTILE ? len : DTILE;
+        s_idx[tid] = u.idx;
+        s_valp[tid] = u.val;
+        s_pre[tid] = u.pre;
+        s_pull[tid] = u.pull;
+    }
+    for (uint32_t x = tid; x < QMAX; x += BLOCK) s_alpha[x] = x ? __fdiv_rn(sw.lr, (float)x) : sw.lr;
+    s_p[tid] = 0;
+
+    uint64_t Z[NW];  // bit q: update q touched this coordinate with a non-zero value
+#pragma unroll
+    for (uint32_t w = 0; w < NW; ++w) Z[w] = 0;
+    bool touched = false;
+
+    // A group of up to 64 consecutive updates: the first 64 entries of each slice go to
+    // registers in one round of requests (wave w: updates g0 + w, g0 + w + WAVES, ...), then the
+    // group passes through LDS DQ updates at a time.
+    constexpr uint32_t GROUP = 64, GW = GROUP / WAVES, PASSES = GROUP / DQ;
+    static_assert(GW == PASSES * PER_WAVE, "a wave's slices of a group, pass by pass");
+    __syncthreads();  // tables ready
+    for (uint32_t g0 = 0; g0 < sw.Q; g0 += GROUP) {
+        uint32_t k[GW], pr[GW];
+        float v[GW];
+        uint32_t have = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < GW; ++j) {
+            // register j: pass j / PER_WAVE, slice wv + (j % PER_WAVE) * WAVES of that pass
+            const uint32_t q = g0 + (j / PER_WAVE) * DQ + wv + (j % PER_WAVE) * WAVES;
+            k[j] = 0;
+            v[j] = 0.f;
+            pr[j] = 0;
+            if (q < sw.Q && lane < s_len[q]) {
+                have |= 1u << j;
+                const uint32_t e = s_b0[q] + lane;
+                k[j] = ((global_u32)s_idx[q])[e];
+                v[j] = ((global_f32)s_valp[q])[e];
+                if (PRE && s_pre[q]) pr[j] = ((global_u32)s_pre[q])[e];
+            }
+        }
+#pragma unroll
+        for (uint32_t p = 0; p < PASSES; ++p) {
+            const uint32_t q0 = g0 + p * DQ;
+            if (q0 >= sw.Q) break;  // uniform
+            const uint32_t nq = sw.Q - q0 < DQ ? sw.Q - q0 : DQ;
+            if (p || g0) __syncthreads();  // the previous pass has been replayed
+#pragma unroll
+            for (uint32_t jj = 0; jj < PER_WAVE; ++jj) {
+                const uint32_t j = p * PER_WAVE + jj, ql = wv + jj * WAVES;
+                const uint32_t c = k[j] - c0;
+                if (((have >> j) & 1u) && c < ncoord) {
+                    s_v[ql][c] = v[j];
+                    if (PRE) s_pr[ql][c] = pr[j];
+                    atomicOr(&s_p[c], 1u << ql);
+                }
+            }
+            for (uint32_t ql = wv; ql < nq; ql += WAVES) {  // slices longer than a wavefront
+                const uint32_t len = s_len[q0 + ql], b0 = s_b0[q0 + ql];
+                for (uint32_t i = WAVE + lane; i < len; i += WAVE) {
+                    const uint32_t e = b0 + i;
+                    const uint32_t c = ((global_u32)s_idx[q0 + ql])[e] - c0;
+                    if (c >= ncoord) continue;
+                    s_v[ql][c] = ((global_f32)s_valp[q0 + ql])[e];
+                    if (PRE) s_pr[ql][c] = s_pre[q0 + ql] ? ((global_u32)s_pre[q0 + ql])[e] : 0u;
+                    atomicOr(&s_p[c], 1u << ql);
+                }
+            }
+            __syncthreads();
+            // replay: the touches of coordinate `tid` by the updates of this pass, in time order
+            uint32_t pm = s_p[tid];
+            s_p[tid] = 0;
+            touched |= pm != 0;
+            while (pm) {
+                const uint32_t ql = (uint32_t)__builtin_ctz(pm);
+                pm &= pm - 1;
+                const uint32_t q = q0 + ql;
+                const float val = s_v[ql][tid];
+                const uint32_t pull = s_pull[q];
+                uint32_t sigma = PRE ? s_pr[ql][tid] : 0u;
+#pragma unroll
+                for (uint32_t w = 0; w < NW; ++w) {  // bits pull .. q-1 of Z, word by word
+                    const uint32_t base = 64 * w;
+                    const uint32_t lo = pull > base ? pull - base : 0u;
+                    const uint32_t hi = q > base ? (q - base < 64u ? q - base : 64u) : 0u;
+                    if (hi > lo) {
+                        const uint64_t upto = hi == 64u ? ~0ull : (1ull << hi) - 1ull;
+                        sigma += popc64(Z[w] & upto & ~((1ull << lo) - 1ull));
+                    }
+                }
+                const float alpha = sigma < QMAX ? s_alpha[sigma] : __fdiv_rn(sw.lr, (float)sigma);
+                th = __fsub_rn(th, __fmul_rn(alpha, val));
+                if (is_nonzero(val)) {
+#pragma unroll
+                    for (uint32_t w = 0; w < NW; ++w)
+                        if ((q >> 6) == w) Z[w] |= 1ull << (q & 63u);
+                }
+            }
+        }
+    }
+    if (touched) pd.theta[c0 + tid] = th;
+}
+
 // Tiles the fast kernel declined: update by update from global memory, one workgroup per
 // tile, with the snapshot scheme of the scatter plan restricted to the tile.
 __global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
@@ -742,6 +892,7 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
 
 struct Layout {
     bool sweep = false;
+    bool dense = false;   // sweep plan: one thread per coordinate (k_sweep_dense)
     uint32_t tile_shift = 0;
     uint64_t ntiles = 0;
     uint32_t n_hist = 0;  // remembered updates this call reaches back to
@@ -813,9 +964,19 @@ void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_updat
         uint32_t shift = 0;
         while ((2u << shift) <= TILE_MAX) ++shift;  // log2(TILE_MAX)
         const double table_budget = std::max(64.0 * 1048576.0, 16.0 * entries);
-        while (shift > 0 && (double)(1u << shift) * per_coord > STAGE_CAP / 2 &&
-               4.0 * (double)Q * (double)tiles_at(shift - 1) <= table_budget)
-            --shift;
+        // ADACOMP_SWEEP_KERNEL=dense|tiled overrides the choice between the two kinds of tile
+        const char *kind = std::getenv("ADACOMP_SWEEP_KERNEL");
+        const bool dense_forced = kind && std::strcmp(kind, "dense") == 0;
+        const bool dense_allowed = !kind || dense_forced;  // "tiled" and "long" name the sorting kernels
+        const bool dense = Q <= DENSE_QMAX && dense_allowed && (dense_forced || per_coord >= (Q <= 64 ? DENSE_PER_COORD : DENSE_PER_COORD_LONG)) &&
+                           (dense_forced || 4.0 * (double)Q * (double)tiles_at(DTILE_SHIFT) <= table_budget);
+        if (dense) {
+            shift = DTILE_SHIFT;
+        } else {
+            while (shift > 0 && (double)(1u << shift) * per_coord > STAGE_CAP / 2 &&
+                   4.0 * (double)Q * (double)tiles_at(shift - 1) <= table_budget)
+                --shift;
+        }
         const uint64_t ntiles = tiles_at(shift);
         uint32_t launches = 0;  // of the scatter plan
         for (uint32_t q = 0; q < Q; ++q)
@@ -825,6 +986,7 @@ void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_updat
         const double scatter_cost = 440.0 * entries + LAUNCH_COST_BYTES * launches;
         if (ntiles < 0x7fffffffull && (always || scatter_cost > sweep_cost)) {
             lay.sweep = true;
+            lay.dense = dense;
             lay.tile_shift = shift;
             lay.ntiles = ntiles;
         }
@@ -853,6 +1015,20 @@ void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_updat
             lay.pre[q] = take((size_t)updates[q].layer_off[L] * sizeof(uint32_t));
     }
     lay.bytes = off;
+}
+
+// Remember the applied updates: slot (timestamp mod history_cap) of the trace.
+void remember(adacomp_state_t *st, const adacomp_update_t *updates, uint32_t Q, uint32_t L, uint64_t t0) {
+    const uint32_t first = Q > st->history_cap ? Q - st->history_cap : 0;
+    for (uint32_t q = first; q < Q; ++q) {
+        const uint64_t slot = (t0 + q) % st->history_cap;
+        uint64_t *off = st->history_off + slot * ((uint64_t)L + 1);
+        std::memcpy(off, updates[q].layer_off, ((size_t)L + 1) * sizeof(uint64_t));
+        st->history[slot] = updates[q];
+        st->history[slot].layer_off = off;
+    }
+    const uint64_t len = (uint64_t)st->history_len + Q;
+    st->history_len = (uint32_t)(len < st->history_cap ? len : st->history_cap);
 }
 
 }  // namespace
@@ -1003,6 +1179,21 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
                        reinterpret_cast<uint32_t *>(wsb + lay.bounds),
                        reinterpret_cast<uint32_t *>(wsb + lay.tile_tensor));
         CHECK_LAUNCH();
+        if (lay.dense) {
+            bool any_pre = false;
+            for (uint32_t q = 0; q < Q; ++q) any_pre = any_pre || lay.pre[q] != SIZE_MAX;
+            const dim3 grid((unsigned)lay.ntiles);
+#define DENSE(NW, DQ, PRE) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, (k_sweep_dense<NW, DQ, PRE>), grid, dim3(BLOCK), s, sw)
+            if (Q <= 64 && any_pre) DENSE(1, 16, true);
+            else if (Q <= 64) DENSE(1, 16, false);
+            else if (any_pre) DENSE(4, 16, true);
+            else DENSE(4, 16, false);
+#undef DENSE
+            CHECK_LAUNCH();
+            if (st->history_cap) remember(st, updates, Q, L, t0);
+            st->t = t0 + Q;
+            return ADACOMP_OK;
+        }
         // several tiles per workgroup once there are enough tiles to fill the chip many times over
         uint32_t tpb = lay.ntiles >= 65536 ? 4u : 1u;
         if (const char *e = std::getenv("ADACOMP_TPB")) tpb = (uint32_t)std::atoi(e);
@@ -1050,19 +1241,7 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         }
     }
 
-    // remember the applied updates: slot (timestamp mod history_cap) of the trace
-    if (st->history_cap) {
-        const uint32_t first = Q > st->history_cap ? Q - st->history_cap : 0;
-        for (uint32_t q = first; q < Q; ++q) {
-            const uint64_t slot = (t0 + q) % st->history_cap;
-            uint64_t *off = st->history_off + slot * ((uint64_t)L + 1);
-            std::memcpy(off, updates[q].layer_off, ((size_t)L + 1) * sizeof(uint64_t));
-            st->history[slot] = updates[q];
-            st->history[slot].layer_off = off;
-        }
-        const uint64_t len = (uint64_t)st->history_len + Q;
-        st->history_len = (uint32_t)(len < st->history_cap ? len : st->history_cap);
-    }
+    if (st->history_cap) remember(st, updates, Q, L, t0);
     st->t = t0 + Q;
     return ADACOMP_OK;
 }

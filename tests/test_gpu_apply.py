@@ -506,7 +506,8 @@ def test_update_validate_and_malformed_entries_are_skipped(ac, dev, monkeypatch)
         assert compare(got, want, f"{plan}: out-of-range entry skipped") == 0
 
 
-@pytest.mark.parametrize("kernel,tpb", [("short", "1"), ("short", "2"), ("short", "4"), ("long", "1"), ("long", "2"), ("long", "4")])
+@pytest.mark.parametrize("kernel,tpb", [("short", "1"), ("short", "2"), ("short", "4"), ("long", "1"), ("long", "2"), ("long", "4"),
+                                        ("dense", "1")])
 def test_sweep_kernels_and_tiles_per_workgroup(ac, dev, monkeypatch, kernel, tpb):
     """The sweep has a kernel for queues of up to 64 updates (all loads of a workgroup's tiles
     requested ahead) and a general one, each working through 1, 2 or 4 tiles per workgroup; forced
@@ -514,8 +515,7 @@ def test_sweep_kernels_and_tiles_per_workgroup(ac, dev, monkeypatch, kernel, tpb
     kernel, zero-valued entries and pulls that reach back across calls: always the oracle's result."""
     monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
     monkeypatch.setenv("ADACOMP_TPB", tpb)
-    if kernel == "long":
-        monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", "long")
+    monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", {"short": "tiled", "long": "long", "dense": "dense"}[kernel])
     rng = np.random.default_rng(7 + int(tpb))
     sizes = [2048 * 5 + 3, 1, 0, 2048 * 2, 70_001]            # 6 + 1 + 0 + 2 + 35 tiles of 2048
     Q = 20
@@ -644,3 +644,29 @@ def test_degenerate_calls(ac, dev):
     ac.adacomp_apply(zero_size, st0, [out], 0.1, ws)
     torch.cuda.synchronize()
     assert out.offsets == [0, 0, 0] and st0.t == 1
+
+
+@pytest.mark.parametrize("Q,density", [(2, 1.0), (17, 0.05), (33, 0.6), (64, 0.3), (64, 1.0), (65, 0.2), (130, 1.0), (200, 0.1),
+                                       (256, 0.4)])
+@pytest.mark.parametrize("kernel", ["dense", "tiled"])
+def test_dense_queues_one_thread_per_coordinate(ac, dev, monkeypatch, Q, density, kernel):
+    """Queues with about one entry per parameter or more go through a sweep kernel of their own (a
+    thread per coordinate, the non-zero touches of a coordinate as a bit mask over the queue) for
+    up to 256 updates.  Forced on and off here, on ragged tensors (sizes 0, 1, 255, 256, 257), with
+    slices longer than a wavefront (density 1), zero-valued entries and pulls that reach back
+    across calls: the oracle's result either way."""
+    monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
+    monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", kernel)
+    rng = np.random.default_rng(9000 + Q)
+    sizes = [1000, 1, 0, 255, 256, 257, 3 * 256 + 100]
+    ups = random_updates(rng, sizes, Q, density, zero_frac=0.15)
+    pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    want = run_oracle(theta0, ups, pulls, 0.03)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.03, dev)
+    assert st.t == Q
+    assert compare(got, want, f"{kernel}: Q={Q} density={density}, one call") == 0
+    if Q >= 3:
+        a = Q // 3
+        got, _, st = run_gpu(ac, theta0, ups, pulls, 0.03, dev, chunks=[a, 1, Q - a - 1], history=Q)
+        assert compare(got, want, f"{kernel}: Q={Q} density={density}, three calls with a trace") == 0
