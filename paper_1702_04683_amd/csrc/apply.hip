@@ -24,7 +24,9 @@
 //            Theta is read and written once per touched coordinate instead of once per
 //            touch.  A tile whose lists do not fit LDS is replayed update by update from
 //            global memory by a second kernel (snapshot scheme on cnt, one workgroup per
-//            such tile).
+//            such tile).  Dense queues (about one queued entry per parameter or more, up to
+//            256 updates) take a kernel of their own that needs no sorting: a thread per
+//            coordinate, the coordinate's non-zero touches as a bit mask over the queue.
 //
 // The part of an update's window that lies before the call is searched in the remembered
 // updates (k_history) and handed to either plan as a per-entry addend.
