@@ -135,8 +135,9 @@ struct Group {
 };
 
 struct Plan {
-    std::vector<LayerDesc> desc;  // L+1, the last one carries the totals
-    std::vector<Group> groups;
+    std::vector<LayerDesc> desc;  // the tensors that go through the pipeline, in order, then one entry with the totals
+    std::vector<uint64_t> off;    // [L+1] first output entry of every tensor of the call
+    std::vector<Group> groups;    // ranges of `desc`
     uint64_t pack_total = 0;
     std::vector<SmallDesc> small; // tensors left to k_small, largest first
     uint64_t nseg_total = 0, cand_total = 0, out_total = 0;
@@ -151,7 +152,8 @@ uint32_t sample_piece(uint32_t p, uint32_t stride, uint32_t npieces) {
 int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double rate,
               const uint64_t *k_override, Plan &plan) {
     if (!(rate >= 0.0 && rate <= 1.0)) return ADACOMP_ERR_RATE;
-    plan.desc.assign((size_t)L + 1, LayerDesc{});
+    plan.desc.clear();
+    plan.off.assign((size_t)L + 1, 0);
     uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, iblk = 0, gblk = 0;
     // one workgroup per small tensor, if together they stay cache-sized (ADACOMP_SELECT_SMALL=0:
     // never, for tests of the pipeline on small tensors)
@@ -172,7 +174,8 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
         if (n[l] > 0xffffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
         uint64_t k64 = k_override ? k_override[l] : adacomp_count(n[l], rate);
         if (k64 > n[l]) return ADACOMP_ERR_K_RANGE;
-        LayerDesc &d = plan.desc[l];
+        LayerDesc d{};
+        plan.off[l] = out;
         d.g = data ? data[l] : nullptr;
         d.n = (uint32_t)n[l];
         d.k = (uint32_t)k64;
@@ -230,9 +233,9 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
                 d.cap = (uint32_t)std::min<uint64_t>(cap, WSEG);
                 const uint64_t slots = (uint64_t)d.nseg * d.cap;
                 if (grp.filters && cand + slots > group_slots_max) {  // close the group, reuse the regions
-                    grp.l1 = l;
+                    grp.l1 = (uint32_t)plan.desc.size();
                     plan.groups.push_back(grp);
-                    grp = Group{l, l, 0};
+                    grp = Group{grp.l1, grp.l1, 0};
                     cand = 0;
                 }
                 d.cand_base = cand;
@@ -247,14 +250,18 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
             seg += d.nseg;
             wblk += (d.nseg + WAVES - 1) / WAVES;
         }
+        // small and empty tensors never reach the pipeline's kernels: no descriptor, nothing to upload
+        if (d.mode != MODE_EMPTY && d.mode != MODE_SMALL) plan.desc.push_back(d);
         out += d.k;
     }
     if (seg > 0xffffffffull || sblk > 0x7fffffffull || wblk > 0x7fffffffull ||
         iblk > 0x7fffffffull || gblk > 0x7fffffffull)
         return ADACOMP_ERR_LAYER_TOO_LARGE;
-    grp.l1 = L;
+    grp.l1 = (uint32_t)plan.desc.size();
     plan.groups.push_back(grp);
-    LayerDesc &e = plan.desc[L];
+    plan.off[L] = out;
+    plan.desc.push_back(LayerDesc{});
+    LayerDesc &e = plan.desc.back();
     e.out_off = out;
     e.cand_base = cand_max;
     e.pack_base = pack;
@@ -272,6 +279,7 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
     return ADACOMP_OK;
 }
 
+// L: the tensors of the pipeline (plan.desc.size() - 1)
 void carve(const Plan &plan, uint32_t L, void *base, Workspace &ws) {
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -1358,7 +1366,7 @@ extern "C" int adacomp_select_workspace(const uint64_t *n, uint32_t L, double ra
     int rc = make_plan(n, nullptr, L, rate, k_override, plan);
     if (rc) return rc;
     Workspace ws;
-    carve(plan, L, nullptr, ws);
+    carve(plan, (uint32_t)plan.desc.size() - 1, nullptr, ws);
     *bytes = ws.bytes;
     return ADACOMP_OK;
 }
@@ -1391,17 +1399,18 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
     if (plan.out_total && (!out->idx || !out->val)) return ADACOMP_ERR_NULL;
     if (((uintptr_t)out->idx & 3u) || ((uintptr_t)out->val & 3u) || ((uintptr_t)out->layer_off_dev & 7u))
         return ADACOMP_ERR_ALIGNMENT;
+    const uint32_t n_tensors = L;
+    L = (uint32_t)plan.desc.size() - 1;  // from here on: the tensors of the pipeline
     Workspace ws;
     carve(plan, L, workspace, ws);
     if (!workspace || ((uintptr_t)workspace & 255u) || ws_bytes < ws.bytes) return ADACOMP_ERR_WORKSPACE;
 
-    std::vector<uint64_t> off((size_t)L + 1);
-    for (uint32_t l = 0; l <= L; ++l) off[l] = out->layer_off[l] = plan.desc[l].out_off;
+    for (uint32_t l = 0; l <= n_tensors; ++l) out->layer_off[l] = plan.off[l];
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (put_async(out->layer_off_dev, off.data(), off.size() * sizeof(uint64_t), s) != hipSuccess)
+    if (put_async(out->layer_off_dev, plan.off.data(), plan.off.size() * sizeof(uint64_t), s) != hipSuccess)
         return ADACOMP_ERR_HIP;
-    if (L == 0) return ADACOMP_OK;
+    if (n_tensors == 0) return ADACOMP_OK;
     const LayerDesc &tot = plan.desc[L];
     uint32_t *out_idx = out->idx;
     uint32_t *out_val = reinterpret_cast<uint32_t *>(out->val);
