@@ -51,7 +51,12 @@ constexpr int FILTER_NLOAD = 2;     // 16-byte loads per lane in flight in the f
 constexpr uint32_t PIECE = 256;     // elements per wave-wide float4 load
 constexpr uint32_t BINS = 4096;     // histogram bins (12 key bits)
 constexpr uint32_t VCHUNK = 2048;   // packed candidates per wave chunk (descent, count, emit)
-constexpr uint32_t GSEGS = 16;      // segments per wave in the gather
+// Segments per wave in the gather, by the capacity of a candidate region (three times its expected fill): fuller
+// regions mean longer chains of loads per segment, so fewer segments per wave and more waves.  Measured per step:
+// capacity 100: 54 us at 16, 66 at 4; 247: 0.42 ms at 8, 0.50 at 16, 0.47 at 4; 410: 0.176 ms at 4, 0.188 at 8,
+// 0.230 at 16; 3260: 1.68 ms at 4, 2.44 at 8, 3.76 at 16.
+constexpr uint32_t GSEGS = 16, GSEGS_MID = 8, GSEGS_FULL = 4;
+constexpr uint32_t GATHER_MID_CAP = 128, GATHER_FULL_CAP = 320;
 constexpr uint32_t TAIL_BLOCKS = 1024;  // workgroups of the descent / count / emit kernels
 constexpr uint32_t SPIECES = 64;    // sampled pieces per sample-histogram workgroup
 constexpr uint32_t BLOCK = 256;     // threads per workgroup = 4 waves
@@ -94,7 +99,7 @@ struct LayerDesc {
     uint32_t sblk_base;  // prefix sums of workgroup counts, one per kernel shape
     uint32_t wblk_base;  //   one segment per wave
     uint32_t iblk_base;  //   identity copy
-    uint32_t gblk_base;  //   GSEGS segments per wave (gather)
+    uint32_t gblk_base;  //   gather: Plan::gsegs segments per wave
     uint32_t pad;
 };
 static_assert(sizeof(LayerDesc) % 8 == 0, "descriptor table is uploaded as 64-bit words");
@@ -138,6 +143,7 @@ struct Plan {
     std::vector<LayerDesc> desc;  // the tensors that go through the pipeline, in order, then one entry with the totals
     std::vector<uint64_t> off;    // [L+1] first output entry of every tensor of the call
     std::vector<Group> groups;    // ranges of `desc`
+    uint32_t gsegs = GSEGS;       // segments per wave in the gather
     uint64_t pack_total = 0;
     std::vector<SmallDesc> small; // tensors left to k_small, largest first
     uint64_t nseg_total = 0, cand_total = 0, out_total = 0;
@@ -154,7 +160,7 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
     if (!(rate >= 0.0 && rate <= 1.0)) return ADACOMP_ERR_RATE;
     plan.desc.clear();
     plan.off.assign((size_t)L + 1, 0);
-    uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, iblk = 0, gblk = 0;
+    uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, iblk = 0;
     // one workgroup per small tensor, if together they stay cache-sized (ADACOMP_SELECT_SMALL=0:
     // never, for tests of the pipeline on small tensors)
     uint64_t small_elems = 0;
@@ -186,7 +192,6 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
         d.sblk_base = (uint32_t)sblk;
         d.wblk_base = (uint32_t)wblk;
         d.iblk_base = (uint32_t)iblk;
-        d.gblk_base = (uint32_t)gblk;
         d.npieces = (uint32_t)((n[l] + PIECE - 1) / PIECE);
         d.stride = 1;
         if (d.n == 0 || d.k == 0) {
@@ -245,7 +250,6 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
                 cand_max = std::max(cand_max, cand);
                 ++grp.filters;
                 sblk += (d.npieces_s + SPIECES - 1) / SPIECES;
-                gblk += (d.nseg + WAVES * GSEGS - 1) / (WAVES * GSEGS);
             }
             seg += d.nseg;
             wblk += (d.nseg + WAVES - 1) / WAVES;
@@ -253,6 +257,16 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
         // small and empty tensors never reach the pipeline's kernels: no descriptor, nothing to upload
         if (d.mode != MODE_EMPTY && d.mode != MODE_SMALL) plan.desc.push_back(d);
         out += d.k;
+    }
+    // the gather's shape follows the fullest regions of the call
+    uint32_t cap_max = 0;
+    for (const LayerDesc &d : plan.desc)
+        if (d.mode == MODE_FILTER) cap_max = std::max(cap_max, d.cap);
+    plan.gsegs = cap_max >= GATHER_FULL_CAP ? GSEGS_FULL : cap_max >= GATHER_MID_CAP ? GSEGS_MID : GSEGS;
+    uint64_t gblk = 0;
+    for (LayerDesc &d : plan.desc) {
+        d.gblk_base = (uint32_t)gblk;
+        if (d.mode == MODE_FILTER) gblk += (d.nseg + WAVES * plan.gsegs - 1) / (WAVES * plan.gsegs);
     }
     if (seg > 0xffffffffull || sblk > 0x7fffffffull || wblk > 0x7fffffffull ||
         iblk > 0x7fffffffull || gblk > 0x7fffffffull)
@@ -672,33 +686,34 @@ __global__ __launch_bounds__(BLOCK) void k_check(Workspace ws, uint32_t l0) {
 }
 
 // ---- step 5: pack the candidate regions of a tensor, in index order ------------------
+template <uint32_t GS>
 __global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L, uint32_t blk0) {
     const uint32_t blk = blk0 + blockIdx.x;
     const uint32_t l = find_layer<&LayerDesc::gblk_base>(ws.desc, L, blk);
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER || ws.state[l].use_dense) return;
     const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
-    const uint32_t s0 = ((blk - d.gblk_base) * WAVES + wave) * GSEGS;
+    const uint32_t s0 = ((blk - d.gblk_base) * WAVES + wave) * GS;
     if (s0 >= d.nseg) return;
     uint32_t my_cnt = 0, my_off = 0;
-    if (lane < GSEGS && s0 + lane < d.nseg) {
+    if (lane < GS && s0 + lane < d.nseg) {
         my_cnt = ws.seg_cnt[d.seg_base + s0 + lane];
         my_off = ws.seg_off[d.seg_base + s0 + lane];
     }
     const uint2 *__restrict__ cand = ws.cand + d.cand_base + (uint64_t)s0 * d.cap;
     uint32_t *__restrict__ pidx = ws.pack_idx + d.pack_base;
     uint32_t *__restrict__ pval = ws.pack_val + d.pack_base;
-    uint32_t cnt[GSEGS], off[GSEGS];
-    uint2 rc[GSEGS];
+    uint32_t cnt[GS], off[GS];
+    uint2 rc[GS];
 #pragma unroll
-    for (uint32_t i = 0; i < GSEGS; ++i) {  // first 64 candidates of every segment, loads together
+    for (uint32_t i = 0; i < GS; ++i) {  // first 64 candidates of every segment, loads together
         cnt[i] = __shfl(my_cnt, i);
         cnt[i] = cnt[i] < d.cap ? cnt[i] : d.cap;
         off[i] = __shfl(my_off, i);
         if (lane < cnt[i]) rc[i] = cand[(uint64_t)i * d.cap + lane];
     }
 #pragma unroll
-    for (uint32_t i = 0; i < GSEGS; ++i) {
+    for (uint32_t i = 0; i < GS; ++i) {
         if (lane < cnt[i]) {
             pidx[off[i] + lane] = rc[i].x;
             pval[off[i] + lane] = rc[i].y;
@@ -1435,7 +1450,10 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
             const uint32_t w0 = plan.desc[g.l0].wblk_base, g0 = plan.desc[g.l0].gblk_base;
             LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, plan.desc[g.l1].wblk_base - w0, ws, L, w0);
             LAUNCH(ADACOMP_KERNEL_CHECK, k_check, g.l1 - g.l0, ws, g.l0);
-            LAUNCH(ADACOMP_KERNEL_GATHER, k_gather, plan.desc[g.l1].gblk_base - g0, ws, L, g0);
+            const uint32_t g_blocks = plan.desc[g.l1].gblk_base - g0;
+            if (plan.gsegs == GSEGS) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS>, g_blocks, ws, L, g0);
+            else if (plan.gsegs == GSEGS_MID) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_MID>, g_blocks, ws, L, g0);
+            else LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_FULL>, g_blocks, ws, L, g0);
         }
     }
     if (tot.seg_base) {
