@@ -102,10 +102,11 @@ typedef struct {
  *   t            i: number of updates applied so far (advanced by adacomp_apply)
  *   cnt          HOST array [num_layers] of DEVICE pointers; cnt[l] holds n_l uint32
  *                counters, one per parameter of tensor l.  Scratch of the library: when a
- *                call executes update by update, every applied non-zero entry for k
- *                increments cnt[l][k], and the part of sigma_k (eq. 3) that lies inside
- *                the call is a difference of two readings of it.  Only differences are
- *                used: the values need no initialisation and mean nothing between calls.
+ *                call executes update by update, an applied non-zero entry for k
+ *                increments cnt[l][k] (unless no later update of the call looks back on
+ *                it), and the part of sigma_k (eq. 3) that lies inside the call is a
+ *                difference of two readings of it.  Only differences are used: the values
+ *                need no initialisation and mean nothing between calls.
  *   history_cap  d: how many applied updates the trace remembers (Sec. 4 "Complexity":
  *                the last d updates, d = the worst delay); 0 = none
  *   history_len  remembered so far (maintained by adacomp_apply)

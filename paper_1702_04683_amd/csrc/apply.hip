@@ -9,7 +9,8 @@
 //            cnt_k(at time j).  The reading cnt_k(j) is taken by a gather ("snapshot") of cnt
 //            at the update's own indices, enqueued where PS time equals the update's pull
 //            timestamp.  Only differences of cnt are used, so its starting values do not
-//            matter.  Indices inside one update are unique, so the scatter needs no atomics.
+//            matter, and an update that no later snapshot of the call looks back on is not
+//            counted at all.  Indices inside one update are unique, so the scatter needs no atomics.
 //            Each random 4-byte access moves a whole cache line: right for short or very
 //            sparse queues.
 //
@@ -153,8 +154,11 @@ __global__ __launch_bounds__(BLOCK) void k_history(const HistDesc *H, uint32_t f
 // One PS iteration.  STALE: the update has a snapshot of the counters taken at its pull time
 // (or at the start of the call if it was pulled earlier); PRE: it was pulled before this call
 // and carries the staleness accumulated until the call.  Without either, sigma_k is 0 or 1
-// for every entry and alpha_k = alpha.
-template <bool STALE, bool PRE>
+// for every entry and alpha_k = alpha.  COUNT: a later update of the call takes the difference
+// of two counter readings around this one, so its non-zero entries must be counted; the last
+// updates of a call (the only one, when the server applies update by update) leave the
+// counters alone.
+template <bool STALE, bool PRE, bool COUNT>
 __global__ __launch_bounds__(BLOCK) void k_scatter_apply(const ParamDesc *P, uint32_t L, const uint64_t *off,
                                                          const uint32_t *idx, const float *val,
                                                          const uint32_t *snap, const uint32_t *pre, uint64_t total,
@@ -173,11 +177,11 @@ __global__ __launch_bounds__(BLOCK) void k_scatter_apply(const ParamDesc *P, uin
         float *theta = P[l].theta + k;
         uint32_t *cnt = P[l].cnt + k;
         uint32_t c = 0, sigma = 0;
-        if (STALE || nonzero) c = *cnt;
+        if (STALE || (COUNT && nonzero)) c = *cnt;
         if (STALE) sigma = c - snap[e];  // eq. 3, the part inside this call
         if (PRE) sigma += pre[e];        // eq. 3, the part before it
         *theta = step(*theta, lr, sigma, v);
-        if (nonzero) *cnt = c + 1;
+        if (COUNT && nonzero) *cnt = c + 1;
     }
 }
 
@@ -1216,6 +1220,13 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
     } else {
         if (L && put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess)
             return ADACOMP_ERR_HIP;
+        // counted[q]: some later update has a snapshot taken at or before update q
+        std::vector<char> counted(Q, 0);
+        uint32_t first_snapshot = UINT32_MAX;
+        for (uint32_t q = Q; q-- > 0;) {
+            counted[q] = first_snapshot <= q;
+            if (stale[q]) first_snapshot = std::min(first_snapshot, pull_rel[q]);
+        }
         for (uint32_t q = 0; q < Q; ++q) {
             for (uint32_t w : pulled_at[q]) {
                 const adacomp_update_t &u = updates[w];
@@ -1231,9 +1242,15 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
             const dim3 grid((unsigned)((total + BLOCK * ITEMS - 1) / (BLOCK * ITEMS)));
             const uint32_t *snap = reinterpret_cast<const uint32_t *>(wsb + lay.snap[q]);
             const uint32_t *pre = pre_of(q);
-#define SCATTER(STALE, PRE)                                                                                       \
-    ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, (k_scatter_apply<STALE, PRE>), grid, dim3(BLOCK), s, P, L,       \
-                   u.layer_off_dev, u.idx, u.val, snap, pre, total, lr)
+#define SCATTER(STALE, PRE)                                                                                        \
+    do {                                                                                                           \
+        if (counted[q])                                                                                            \
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, (k_scatter_apply<STALE, PRE, true>), grid, dim3(BLOCK),   \
+                           s, P, L, u.layer_off_dev, u.idx, u.val, snap, pre, total, lr);                          \
+        else                                                                                                       \
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_SCATTER_APPLY, (k_scatter_apply<STALE, PRE, false>), grid, dim3(BLOCK),  \
+                           s, P, L, u.layer_off_dev, u.idx, u.val, snap, pre, total, lr);                          \
+    } while (0)
             if (stale[q] && pre) SCATTER(true, true);
             else if (stale[q]) SCATTER(true, false);
             else if (pre) SCATTER(false, true);
