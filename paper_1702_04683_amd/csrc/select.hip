@@ -13,12 +13,14 @@
 //   3. filter             the one full streaming read: every wave owns a contiguous
 //                         8192-element segment and compacts, in index order, the
 //                         entries with key >= t_lo into its own candidate region;
-//   4. check              per tensor: scan of the region fill counts; a tensor whose
-//                         candidates are fewer than k, overflowed a region or exceed a
-//                         quarter of the tensor is switched to the dense source (the
-//                         tensor itself), so exactness never depends on the sample;
+//   4. check              per tensor: scan of the candidate counts; a tensor whose
+//                         candidates are fewer than k or exceed a quarter of the tensor
+//                         is switched to the dense source (the tensor itself), so
+//                         exactness never depends on the sample;
 //   5. gather             the regions are packed, in index order, into one dense
-//                         (index, value) array per tensor;
+//                         (index, value) array per tensor; a segment with more
+//                         candidates than its region holds (large entries clustered in
+//                         one stretch) is read and filtered again on the spot;
 //   6. radix descent      12 + 12 + 7 bit histograms over the packed candidates (or the
 //                         dense source) give the exact threshold key T and tie quota r;
 //   7. count / scan / emit  per-chunk counts of key > T and key == T, their exclusive
@@ -113,6 +115,8 @@ struct LayerState {
     uint32_t r;          // number of entries with key == T to keep (lowest indices)
     uint32_t m;          // elements of the source the descent reads: n, or the number of candidates
     uint32_t nchunk;     // chunks of that source (WSEG elements of the tensor, VCHUNK candidates)
+    uint32_t t_reserve;  // a lower, safer threshold the filter only counts against (<= t_lo)
+    uint32_t refilter;   // t_lo fell short and was replaced by t_reserve: the gather filters every segment again
 };
 
 struct Workspace {
@@ -120,6 +124,7 @@ struct Workspace {
     LayerState *state;    // [L]
     uint32_t *hist;       // [L][BINS]
     uint32_t *seg_cnt;    // [nseg_total] candidates found per segment
+    uint32_t *seg_res;    // [nseg_total] entries with key >= t_reserve per segment
     uint32_t *seg_gt;     // [nseg_total] #key > T, then exclusive prefix within the tensor
     uint32_t *seg_eq;     // [nseg_total] #key == T, then exclusive prefix within the tensor
     uint32_t *chunk_base; // [L+1] first chunk of every tensor in the global chunk numbering
@@ -305,6 +310,7 @@ void carve(const Plan &plan, uint32_t L, void *base, Workspace &ws) {
     ws.state = (LayerState *)take((size_t)L * sizeof(LayerState));
     ws.hist = (uint32_t *)take((size_t)L * BINS * sizeof(uint32_t));
     ws.seg_cnt = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
+    ws.seg_res = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
     ws.seg_gt = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
     ws.seg_eq = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
     ws.chunk_base = (uint32_t *)take(((size_t)L + 1) * sizeof(uint32_t));
@@ -555,16 +561,28 @@ __global__ __launch_bounds__(BLOCK) void k_pick(Workspace ws) {
     const uint32_t l = blockIdx.x;
     const LayerDesc d = ws.desc[l];
     uint32_t *h = ws.hist + (size_t)l * BINS;
-    uint32_t t_lo = 0;
+    uint32_t t_lo = 0, t_reserve = 0;
     if (d.mode == MODE_FILTER) {
         uint32_t bin, above;
         find_bin_from_top(h, BINS, d.target, bin, above);
         t_lo = bin << 19;
+        t_reserve = t_lo;
+        if (d.stride > 1) {
+            // The margin in d.target is that of independent draws.  Where large entries cluster (rows
+            // of a weight matrix), a sample of 1 KB pieces can be off by far more: the filter also
+            // counts against the threshold that three times as many sampled entries reach, and
+            // check / gather fall back on that one before giving up on the candidates altogether.
+            const uint32_t wide = d.target > 0x55555555u ? 0xffffffffu : 3u * d.target;
+            find_bin_from_top(h, BINS, wide, bin, above);
+            t_reserve = bin << 19;
+        }
         for (uint32_t i = threadIdx.x; i < BINS; i += BLOCK) h[i] = 0;
     }
     if (threadIdx.x == 0) {
         LayerState st;
         st.t_lo = t_lo;
+        st.t_reserve = t_reserve;
+        st.refilter = 0;
         st.use_dense = d.mode == MODE_DENSE;
         st.prefix = 0;
         st.k_rem = d.k;
@@ -596,7 +614,8 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L, uint
     const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
     const uint32_t seg = (blk - d.wblk_base) * WAVES + wave;
     if (seg >= d.nseg) return;
-    const uint32_t t_lo = ws.state[l].t_lo;
+    const uint32_t t_lo = ws.state[l].t_lo, t_reserve = ws.state[l].t_reserve;
+    uint32_t reserve = 0;  // entries with key >= t_reserve (wave-uniform)
     uint2 *region = ws.cand + d.cand_base + (uint64_t)seg * d.cap;
     uint2 *stage = s_stage[wave];
     const uint32_t cap = d.cap;
@@ -636,6 +655,7 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L, uint
         for (int c = 0; c < 4; ++c) {
             f[c] = (uint32_t)c < nvalid && mag_key(bits[c]) >= t_lo;
             m[c] = __ballot(f[c]);
+            reserve += popc64(__ballot((uint32_t)c < nvalid && mag_key(bits[c]) >= t_reserve));
         }
         if ((m[0] | m[1] | m[2] | m[3]) == 0) return;
         const uint32_t found = popc64(m[0]) + popc64(m[1]) + popc64(m[2]) + popc64(m[3]);
@@ -648,39 +668,55 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L, uint
         staged += found;
     });
     flush(true);
-    if (lane == 0) ws.seg_cnt[d.seg_base + seg] = written;
+    if (lane == 0) {
+        ws.seg_cnt[d.seg_base + seg] = written;
+        ws.seg_res[d.seg_base + seg] = reserve;
+    }
 }
 
 // ---- step 4: candidate offsets per segment; are the candidates usable? -------------
 __global__ __launch_bounds__(BLOCK) void k_check(Workspace ws, uint32_t l0) {
     __shared__ uint32_t s_wave[WAVES];
-    __shared__ uint32_t s_over;
     const uint32_t l = l0 + blockIdx.x;
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER) return;
-    if (threadIdx.x == 0) s_over = 0;
-    __syncthreads();
     uint32_t carry = 0;
-    bool over = false;
     for (uint32_t s0 = 0; s0 < d.nseg; s0 += BLOCK) {
         const uint32_t s = s0 + threadIdx.x;
-        uint32_t c = s < d.nseg ? ws.seg_cnt[d.seg_base + s] : 0u;
-        over |= c > d.cap;
-        c = c < d.cap ? c : d.cap;
+        // the count is exact also where the region overflowed (the gather reads such a segment again)
+        const uint32_t c = s < d.nseg ? ws.seg_cnt[d.seg_base + s] : 0u;
         uint32_t total;
         const uint32_t o = block_exclusive_scan<WAVES>(c, s_wave, total);
         if (s < d.nseg) ws.seg_off[d.seg_base + s] = carry + o;
         carry += total;  // cannot wrap: at most n candidates
     }
-    if (over) s_over = 1;
-    __syncthreads();
+    uint32_t m = carry;
+    const uint64_t room = std::min<uint64_t>((uint64_t)d.nseg * d.cap, d.n / 4);  // what the packed array holds, and is worth packing
+    bool refilter = false;
+    if (m < d.k) {
+        // the sample misjudged: the candidates of the reserve threshold, which the filter only counted
+        carry = 0;
+        for (uint32_t s0 = 0; s0 < d.nseg; s0 += BLOCK) {
+            const uint32_t s = s0 + threadIdx.x;
+            const uint32_t c = s < d.nseg ? ws.seg_res[d.seg_base + s] : 0u;
+            uint32_t total;
+            const uint32_t o = block_exclusive_scan<WAVES>(c, s_wave, total);
+            if (s < d.nseg && carry + (uint64_t)o <= room) ws.seg_off[d.seg_base + s] = carry + o;
+            carry += total;
+        }
+        m = carry;
+        refilter = true;
+    }
     if (threadIdx.x == 0) {
-        const uint32_t m = carry;
-        if (s_over || m < d.k || m > d.n / 4) {
+        if (m < d.k || m > room) {
             ws.state[l].use_dense = 1;  // m and nchunk keep the dense-source values
         } else {
             ws.state[l].m = m;
             ws.state[l].nchunk = (m + VCHUNK - 1) / VCHUNK;
+            if (refilter) {
+                ws.state[l].t_lo = ws.state[l].t_reserve;
+                ws.state[l].refilter = 1;
+            }
         }
     }
 }
@@ -695,9 +731,10 @@ __global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L, uint
     const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
     const uint32_t s0 = ((blk - d.gblk_base) * WAVES + wave) * GS;
     if (s0 >= d.nseg) return;
+    const bool refilter_all = ws.state[l].refilter != 0;  // the regions hold the candidates of a threshold that fell short
     uint32_t my_cnt = 0, my_off = 0;
     if (lane < GS && s0 + lane < d.nseg) {
-        my_cnt = ws.seg_cnt[d.seg_base + s0 + lane];
+        my_cnt = refilter_all ? 0xffffffffu : ws.seg_cnt[d.seg_base + s0 + lane];
         my_off = ws.seg_off[d.seg_base + s0 + lane];
     }
     const uint2 *__restrict__ cand = ws.cand + d.cand_base + (uint64_t)s0 * d.cap;
@@ -705,10 +742,14 @@ __global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L, uint
     uint32_t *__restrict__ pval = ws.pack_val + d.pack_base;
     uint32_t cnt[GS], off[GS];
     uint2 rc[GS];
+    uint32_t overflowed = 0;  // segments whose region could not hold their candidates (bit i)
 #pragma unroll
     for (uint32_t i = 0; i < GS; ++i) {  // first 64 candidates of every segment, loads together
         cnt[i] = __shfl(my_cnt, i);
-        cnt[i] = cnt[i] < d.cap ? cnt[i] : d.cap;
+        if (cnt[i] > d.cap) {
+            overflowed |= 1u << i;
+            cnt[i] = 0;
+        }
         off[i] = __shfl(my_off, i);
         if (lane < cnt[i]) rc[i] = cand[(uint64_t)i * d.cap + lane];
     }
@@ -729,6 +770,38 @@ __global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L, uint
                 pidx[off[i] + e + WAVE] = c1.x;
                 pval[off[i] + e + WAVE] = c1.y;
             }
+        }
+    }
+    // A region that overflowed (large entries clustered in one stretch of the tensor) holds only
+    // the first `cap` candidates of its segment: the segment is read and filtered again,
+    // straight into the packed arrays.  Only these segments pay for it.
+    if (overflowed) {
+        const uint32_t t_lo = ws.state[l].t_lo;
+        const Source src{reinterpret_cast<const uint32_t *>(d.g), nullptr, d.n, WSEG, d.vec != 0};
+        for (uint32_t i = 0; i < GS; ++i) {
+            if (!((overflowed >> i) & 1u)) continue;
+            const uint32_t lo = (s0 + i) * WSEG;
+            const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
+            uint32_t pos = __shfl(my_off, i);
+            visit_range<false, false, 4>(src, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+                bool f[4];
+                uint64_t m[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    f[c] = (uint32_t)c < nvalid && mag_key(bits[c]) >= t_lo;
+                    m[c] = __ballot(f[c]);
+                }
+                uint32_t p = pos + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (f[c]) {
+                        pidx[p] = idx[c];
+                        pval[p] = bits[c];
+                        ++p;
+                    }
+                }
+                pos += popc64(m[0]) + popc64(m[1]) + popc64(m[2]) + popc64(m[3]);
+            });
         }
     }
 }

@@ -132,9 +132,10 @@ def test_degenerate_tensors(ac, dev, n):
     check(ac, tensors, 0.5, k_override=[1, 2, 3, n - 1, 1, 0, 4, 3, n // 2], what="degenerate k_override")
 
 
-def test_clustered_large_values_fall_back_to_the_dense_source(ac, dev):
+def test_clustered_large_values_overflow_their_regions(ac, dev):
     """All large entries sit in one contiguous stretch, so wave segments there overflow their
-    candidate regions while a strided sample misjudges the threshold: the result must stay exact."""
+    candidate regions (the gather filters those segments again) while a strided sample misjudges
+    the threshold (too few candidates: the tensor itself is read instead): the result must stay exact."""
     n = 2_000_003
     gen = torch.Generator(device=dev).manual_seed(11)
     g = torch.randn(n, generator=gen, device=dev) * 1e-3
@@ -143,6 +144,14 @@ def test_clustered_large_values_fall_back_to_the_dense_source(ac, dev):
     h[::8192] *= 1000.0      # large entries only where a strided sample rarely looks
     for rate in (0.01, 0.002):
         check(ac, [g, h], rate, what="clustered")
+    # every fourth segment dense with large entries, ragged end inside such a segment, unaligned start
+    n = 8192 * 41 + 1234
+    base = torch.randn(n + 1, generator=gen, device=dev) * 1e-3
+    for s0 in range(0, n, 4 * 8192):
+        base[s0 + 100:s0 + 8000] = torch.randn(7900, generator=gen, device=dev)
+    base[8192 * 40:] = torch.randn(base.numel() - 8192 * 40, generator=gen, device=dev) * 3.0
+    for rate in (0.02, 0.1, 0.2):
+        check(ac, [base[:n], base[1:]], rate, what="overflowing segments")
 
 
 def test_unaligned_tensor_views(ac, dev):
