@@ -344,3 +344,36 @@ def test_two_streams_at_once(ac, dev):
     torch.cuda.synchronize()
     for i in range(2):
         assert_update_equal(update_to_host(outs[i]), oracle.select(host(g[i]), 0.01), f"stream {i}")
+
+
+def _sampled_pieces(n):
+    """The 1 KB pieces (256 elements) of an n-element tensor that the sample histogram reads: a
+    white-box copy of the library's choice, so that a test can bias exactly what the sample sees."""
+    npieces = (n + 255) // 256
+    stride = 64
+    while stride > 1 and npieces // stride < 512:
+        stride >>= 1
+    slots = (npieces + stride - 1) // stride
+    p = np.arange(slots, dtype=np.uint64)
+    jit = ((p * 2654435761) & 0xffffffff) >> 16 & (stride - 1)
+    return np.minimum(p * stride + jit, npieces - 1), stride
+
+
+@pytest.mark.parametrize("bias,what", [(1.12, "the reserve threshold takes over"), (1.6, "the tensor itself is read"),
+                                       (0.8, "more candidates than needed")])
+def test_sample_that_misjudges_the_threshold(ac, dev, bias, what):
+    """Everything the sample reads is scaled by `bias`, nothing else: above 1 the sampled threshold
+    is too high and the filter finds fewer than k candidates (slightly: the lower threshold it
+    counted against has enough; grossly: the descent reads the tensor itself), below 1 too low.
+    Row-scaled gradients (large entries clustered in rows) produce the same situations by chance."""
+    n = 4_000_037
+    gen = torch.Generator(device=dev).manual_seed(77)
+    g = torch.randn(n, generator=gen, device=dev) * 1e-3
+    pieces, stride = _sampled_pieces(n)
+    assert stride > 1
+    idx = (torch.from_numpy(pieces.astype(np.int64)).to(dev)[:, None] * 256 + torch.arange(256, device=dev)[None, :]).flatten()
+    idx = idx[idx < n]
+    g[idx] *= bias
+    check(ac, [g], 0.005, what=what)
+    rows = workloads.gradient("mid", 3, device=dev, layers=[5, 6], row_spread=1.5)
+    check(ac, rows, 0.005, what="row-scaled gradient")
