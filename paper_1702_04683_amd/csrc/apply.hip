@@ -23,9 +23,10 @@
 //            pulled at j, sigma_k is the number of earlier non-zero touches of k by updates
 //            u with j <= u < q: eq. 3 evaluated on the tile's own lists; cnt is not needed.
 //            Theta is read and written once per touched coordinate instead of once per
-//            touch.  A tile whose lists do not fit LDS is replayed update by update from
-//            global memory by a second kernel (snapshot scheme on cnt, one workgroup per
-//            such tile).  Dense queues (about one queued entry per parameter or more, up to
+//            touch.  A tile whose lists do not fit LDS is replayed update by update by a
+//            second kernel, one workgroup per such tile (queues of up to 64 updates: out of
+//            LDS, with a mask of non-zero touches per coordinate; longer ones: from global
+//            memory, snapshot scheme on cnt).  Dense queues (about one queued entry per parameter or more, up to
 //            256 updates) take a kernel of their own that needs no sorting: a thread per
 //            coordinate, the coordinate's non-zero touches as a bit mask over the queue.
 //
@@ -894,6 +895,94 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
     }
 }
 
+// Tiles the sorting kernels declined, for queues of at most 64 updates: where the same rows are
+// large in every worker's gradient, a tile holds thousands of queued entries.  The tile's
+// parameters stay in LDS while the queue is replayed update by update; sigma_k is a population
+// count over the coordinate's mask of non-zero touches, as in the kernel for dense queues, so no
+// counters and no snapshots are read or written.  The first 256 entries of the next update's
+// slice are requested before the current update is applied.
+__global__ __launch_bounds__(BLOCK) void k_sweep_hot(Sweep sw) {
+    constexpr uint32_t QMAX = 64;
+    __shared__ float s_theta[TILE_MAX];
+    __shared__ uint64_t s_Z[TILE_MAX];
+    __shared__ const uint32_t *s_idx[QMAX];
+    __shared__ const float *s_valp[QMAX];
+    __shared__ const uint32_t *s_pre[QMAX];
+    __shared__ uint32_t s_b0[QMAX], s_len[QMAX], s_pull[QMAX];
+    __shared__ float s_alpha[QMAX];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n_ovf = sw.ovf[0];
+    const uint32_t tile = 1u << sw.tile_shift;
+    if (tid < sw.Q) {
+        const UpdDesc u = sw.U[tid];
+        s_idx[tid] = u.idx;
+        s_valp[tid] = u.val;
+        s_pre[tid] = u.pre;
+        s_pull[tid] = u.pull;
+    }
+    if (tid < QMAX) s_alpha[tid] = tid ? __fdiv_rn(sw.lr, (float)tid) : sw.lr;
+    for (uint32_t o = blockIdx.x; o < n_ovf; o += gridDim.x) {
+        const uint32_t t = sw.ovf[1 + o];
+        const ParamDesc pd = sw.P[sw.tile_tensor[t]];
+        const uint32_t c0 = (t - (uint32_t)pd.tile_base) << sw.tile_shift;
+        const uint32_t ncoord = pd.n - c0 < tile ? (uint32_t)(pd.n - c0) : tile;
+        __syncthreads();  // tables ready; the previous tile has been written back
+        for (uint32_t c = tid; c < ncoord; c += BLOCK) {
+            s_theta[c] = pd.theta[c0 + c];
+            s_Z[c] = 0;
+        }
+        if (tid < sw.Q) {
+            const uint32_t *row = sw.B + (uint64_t)tid * (sw.ntiles + 1) + t;
+            const uint32_t b0 = row[0], b1 = row[1];
+            s_b0[tid] = b0;
+            const uint32_t len = b1 >= b0 ? b1 - b0 : 0u;  // bounds of an unsorted (malformed) list may cross
+            s_len[tid] = len < tile ? len : tile;          // a sorted list has at most one entry per coordinate
+        }
+        __syncthreads();
+        auto apply_entry = [&](uint32_t q, uint64_t window, uint32_t k, float v, uint32_t before) {
+            const uint32_t c = k - c0;
+            if (c >= ncoord) return;  // only a malformed (unsorted) index list gets here
+            const uint32_t sigma = before + popc64(s_Z[c] & window);
+            const float alpha = sigma < QMAX ? s_alpha[sigma] : __fdiv_rn(sw.lr, (float)sigma);
+            s_theta[c] = __fsub_rn(s_theta[c], __fmul_rn(alpha, v));
+            if (is_nonzero(v)) s_Z[c] |= 1ull << q;
+        };
+        uint32_t next_k = 0, next_before = 0;
+        float next_v = 0.f;
+        bool next_have = tid < s_len[0];
+        if (next_have) {
+            const uint32_t e = s_b0[0] + tid;
+            next_k = ((global_u32)s_idx[0])[e];
+            next_v = ((global_f32)s_valp[0])[e];
+            if (s_pre[0]) next_before = ((global_u32)s_pre[0])[e];
+        }
+        for (uint32_t q = 0; q < sw.Q; ++q) {
+            const uint32_t k = next_k, before = next_before;
+            const float v = next_v;
+            const bool have = next_have;
+            next_have = q + 1 < sw.Q && tid < s_len[q + 1];
+            next_before = 0;
+            if (next_have) {
+                const uint32_t e = s_b0[q + 1] + tid;
+                next_k = ((global_u32)s_idx[q + 1])[e];
+                next_v = ((global_f32)s_valp[q + 1])[e];
+                if (s_pre[q + 1]) next_before = ((global_u32)s_pre[q + 1])[e];
+            }
+            const uint32_t pull = s_pull[q];
+            const uint64_t window = (q ? (1ull << q) - 1ull : 0ull) & ~((1ull << pull) - 1ull);  // updates pull .. q-1
+            if (have) apply_entry(q, window, k, v, before);
+            const uint32_t len = s_len[q], b0 = s_b0[q];
+            for (uint32_t i = BLOCK + tid; i < len; i += BLOCK) {  // slices longer than the workgroup
+                const uint32_t e = b0 + i;
+                apply_entry(q, window, ((global_u32)s_idx[q])[e], ((global_f32)s_valp[q])[e],
+                            s_pre[q] ? ((global_u32)s_pre[q])[e] : 0u);
+            }
+            __syncthreads();
+        }
+        for (uint32_t c = tid; c < ncoord; c += BLOCK) pd.theta[c0 + c] = s_theta[c];
+    }
+}
+
 // ------------------------------------------------------------------ host side
 
 struct Layout {
@@ -1214,8 +1303,12 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
         else if (tpb == 2) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep<2>, grid, dim3(BLOCK), s, sw);
         else ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep<1>, dim3((unsigned)lay.ntiles), dim3(BLOCK), s, sw);
         CHECK_LAUNCH();
-        ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP_SLOW, k_sweep_slow,
-                       dim3((unsigned)std::min<uint64_t>(lay.ntiles, SLOW_GRID)), dim3(BLOCK), s, sw);
+        if (Q <= 64)
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP_SLOW, k_sweep_hot,
+                           dim3((unsigned)std::min<uint64_t>(lay.ntiles, 2 * SLOW_GRID)), dim3(BLOCK), s, sw);
+        else
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP_SLOW, k_sweep_slow,
+                           dim3((unsigned)std::min<uint64_t>(lay.ntiles, SLOW_GRID)), dim3(BLOCK), s, sw);
         CHECK_LAUNCH();
     } else {
         if (L && put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess)
