@@ -675,36 +675,46 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L, uint
 }
 
 // ---- step 4: candidate offsets per segment; are the candidates usable? -------------
-__global__ __launch_bounds__(BLOCK) void k_check(Workspace ws, uint32_t l0) {
-    __shared__ uint32_t s_wave[WAVES];
+// One workgroup per tensor.  A tensor of a billion elements has 122,000 segments: 1024 threads
+// with 4 consecutive counts each, so that the serial part is tens of rounds, not hundreds.
+constexpr uint32_t CBLOCK = 1024, CITEMS = 4;
+
+// seg_off[s] = sum of counts[0..s) for the segments of tensor d; returns the total (same in all threads).
+__device__ __forceinline__ uint32_t scan_segments(const LayerDesc &d, const uint32_t *counts, uint32_t *seg_off,
+                                                  uint32_t *s_wave) {
+    uint32_t carry = 0;
+    for (uint32_t s0 = 0; s0 < d.nseg; s0 += CBLOCK * CITEMS) {
+        const uint32_t s = s0 + threadIdx.x * CITEMS;
+        uint32_t c[CITEMS], sum = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < CITEMS; ++j) {
+            c[j] = s + j < d.nseg ? counts[d.seg_base + s + j] : 0u;
+            sum += c[j];
+        }
+        uint32_t total;
+        uint32_t run = carry + block_exclusive_scan<CBLOCK / WAVE>(sum, s_wave, total);
+#pragma unroll
+        for (uint32_t j = 0; j < CITEMS; ++j) {
+            if (s + j < d.nseg) seg_off[d.seg_base + s + j] = run;
+            run += c[j];
+        }
+        carry += total;  // cannot wrap: at most n candidates
+    }
+    return carry;
+}
+
+__global__ __launch_bounds__(CBLOCK) void k_check(Workspace ws, uint32_t l0) {
+    __shared__ uint32_t s_wave[CBLOCK / WAVE];
     const uint32_t l = l0 + blockIdx.x;
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER) return;
-    uint32_t carry = 0;
-    for (uint32_t s0 = 0; s0 < d.nseg; s0 += BLOCK) {
-        const uint32_t s = s0 + threadIdx.x;
-        // the count is exact also where the region overflowed (the gather reads such a segment again)
-        const uint32_t c = s < d.nseg ? ws.seg_cnt[d.seg_base + s] : 0u;
-        uint32_t total;
-        const uint32_t o = block_exclusive_scan<WAVES>(c, s_wave, total);
-        if (s < d.nseg) ws.seg_off[d.seg_base + s] = carry + o;
-        carry += total;  // cannot wrap: at most n candidates
-    }
-    uint32_t m = carry;
+    // the count is exact also where the region overflowed (the gather reads such a segment again)
+    uint32_t m = scan_segments(d, ws.seg_cnt, ws.seg_off, s_wave);
     const uint64_t room = std::min<uint64_t>((uint64_t)d.nseg * d.cap, d.n / 4);  // what the packed array holds, and is worth packing
     bool refilter = false;
     if (m < d.k) {
         // the sample misjudged: the candidates of the reserve threshold, which the filter only counted
-        carry = 0;
-        for (uint32_t s0 = 0; s0 < d.nseg; s0 += BLOCK) {
-            const uint32_t s = s0 + threadIdx.x;
-            const uint32_t c = s < d.nseg ? ws.seg_res[d.seg_base + s] : 0u;
-            uint32_t total;
-            const uint32_t o = block_exclusive_scan<WAVES>(c, s_wave, total);
-            if (s < d.nseg && carry + (uint64_t)o <= room) ws.seg_off[d.seg_base + s] = carry + o;
-            carry += total;
-        }
-        m = carry;
+        m = scan_segments(d, ws.seg_res, ws.seg_off, s_wave);
         refilter = true;
     }
     if (threadIdx.x == 0) {
@@ -1522,7 +1532,8 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
             if (!g.filters) continue;
             const uint32_t w0 = plan.desc[g.l0].wblk_base, g0 = plan.desc[g.l0].gblk_base;
             LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, plan.desc[g.l1].wblk_base - w0, ws, L, w0);
-            LAUNCH(ADACOMP_KERNEL_CHECK, k_check, g.l1 - g.l0, ws, g.l0);
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_CHECK, k_check, dim3(g.l1 - g.l0), dim3(CBLOCK), s, ws, g.l0);
+            if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
             const uint32_t g_blocks = plan.desc[g.l1].gblk_base - g0;
             if (plan.gsegs == GSEGS) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS>, g_blocks, ws, L, g0);
             else if (plan.gsegs == GSEGS_MID) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_MID>, g_blocks, ws, L, g0);
