@@ -679,26 +679,27 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L, uint
 // with 4 consecutive counts each, so that the serial part is tens of rounds, not hundreds.
 constexpr uint32_t CBLOCK = 1024, CITEMS = 4;
 
-// seg_off[s] = sum of counts[0..s) for the segments of tensor d; returns the total (same in all threads).
-__device__ __forceinline__ uint32_t scan_segments(const LayerDesc &d, const uint32_t *counts, uint32_t *seg_off,
-                                                  uint32_t *s_wave) {
+// out[i] = load(0) + ... + load(i - 1) for i < n, by one workgroup of CBLOCK threads; returns the
+// total (the same in all threads).  `out` may be the array that `load` reads.
+template <class Load>
+__device__ __forceinline__ uint32_t scan_array(Load load, uint32_t *out, uint32_t n, uint32_t *s_wave) {
     uint32_t carry = 0;
-    for (uint32_t s0 = 0; s0 < d.nseg; s0 += CBLOCK * CITEMS) {
-        const uint32_t s = s0 + threadIdx.x * CITEMS;
+    for (uint32_t i0 = 0; i0 < n; i0 += CBLOCK * CITEMS) {
+        const uint32_t i = i0 + threadIdx.x * CITEMS;
         uint32_t c[CITEMS], sum = 0;
 #pragma unroll
         for (uint32_t j = 0; j < CITEMS; ++j) {
-            c[j] = s + j < d.nseg ? counts[d.seg_base + s + j] : 0u;
+            c[j] = i + j < n ? load(i + j) : 0u;
             sum += c[j];
         }
         uint32_t total;
         uint32_t run = carry + block_exclusive_scan<CBLOCK / WAVE>(sum, s_wave, total);
 #pragma unroll
         for (uint32_t j = 0; j < CITEMS; ++j) {
-            if (s + j < d.nseg) seg_off[d.seg_base + s + j] = run;
+            if (i + j < n) out[i + j] = run;
             run += c[j];
         }
-        carry += total;  // cannot wrap: at most n candidates
+        carry += total;  // the callers' sums stay below 2^32
     }
     return carry;
 }
@@ -709,12 +710,13 @@ __global__ __launch_bounds__(CBLOCK) void k_check(Workspace ws, uint32_t l0) {
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER) return;
     // the count is exact also where the region overflowed (the gather reads such a segment again)
-    uint32_t m = scan_segments(d, ws.seg_cnt, ws.seg_off, s_wave);
+    const uint32_t *cnt = ws.seg_cnt + d.seg_base, *res = ws.seg_res + d.seg_base;
+    uint32_t m = scan_array([&](uint32_t i) { return cnt[i]; }, ws.seg_off + d.seg_base, d.nseg, s_wave);
     const uint64_t room = std::min<uint64_t>((uint64_t)d.nseg * d.cap, d.n / 4);  // what the packed array holds, and is worth packing
     bool refilter = false;
     if (m < d.k) {
         // the sample misjudged: the candidates of the reserve threshold, which the filter only counted
-        m = scan_segments(d, ws.seg_res, ws.seg_off, s_wave);
+        m = scan_array([&](uint32_t i) { return res[i]; }, ws.seg_off + d.seg_base, d.nseg, s_wave);
         refilter = true;
     }
     if (threadIdx.x == 0) {
@@ -1159,18 +1161,10 @@ __global__ __launch_bounds__(SBLOCK) void k_small(const SmallDesc *S, uint32_t *
 // ---- chunk numbering across tensors ------------------------------------------------
 // The descent, count and emit kernels run with a fixed number of workgroups; each worker
 // (workgroup or wave) takes a contiguous range of the global chunk numbering.
-__global__ __launch_bounds__(BLOCK) void k_work(Workspace ws, uint32_t L) {
-    __shared__ uint32_t s_wave[WAVES];
-    uint32_t carry = 0;
-    for (uint32_t l0 = 0; l0 < L; l0 += BLOCK) {
-        const uint32_t l = l0 + threadIdx.x;
-        const uint32_t c = l < L ? ws.state[l].nchunk : 0u;
-        uint32_t total;
-        const uint32_t o = block_exclusive_scan<WAVES>(c, s_wave, total);
-        if (l < L) ws.chunk_base[l] = carry + o;
-        carry += total;
-    }
-    if (threadIdx.x == 0) ws.chunk_base[L] = carry;
+__global__ __launch_bounds__(CBLOCK) void k_work(Workspace ws, uint32_t L) {
+    __shared__ uint32_t s_wave[CBLOCK / WAVE];
+    const uint32_t total = scan_array([&](uint32_t l) { return ws.state[l].nchunk; }, ws.chunk_base, L, s_wave);
+    if (threadIdx.x == 0) ws.chunk_base[L] = total;
 }
 
 // Range of global chunk numbers of worker `w` out of `nworkers`, and the tensor of its first chunk.
@@ -1303,27 +1297,15 @@ __global__ __launch_bounds__(BLOCK) void k_count(Workspace ws, uint32_t L) {
 }
 
 // Exclusive scan over the chunks of one tensor of both count arrays, in place.
-__global__ __launch_bounds__(BLOCK) void k_scan(Workspace ws) {
-    __shared__ uint32_t s_wave[WAVES];
+__global__ __launch_bounds__(CBLOCK) void k_scan(Workspace ws) {
+    __shared__ uint32_t s_wave[CBLOCK / WAVE];
     const uint32_t l = blockIdx.x;
     const LayerDesc d = ws.desc[l];
     if (d.nseg == 0) return;
     const uint32_t nchunk = ws.state[l].nchunk;
     uint32_t *gt = ws.seg_gt + d.seg_base, *eq = ws.seg_eq + d.seg_base;
-    uint32_t carry_a = 0, carry_b = 0;
-    for (uint32_t s0 = 0; s0 < nchunk; s0 += BLOCK) {
-        const uint32_t s = s0 + threadIdx.x;
-        const uint32_t a = s < nchunk ? gt[s] : 0u, b = s < nchunk ? eq[s] : 0u;
-        uint32_t ta, tb;
-        const uint32_t xa = block_exclusive_scan<WAVES>(a, s_wave, ta);
-        const uint32_t xb = block_exclusive_scan<WAVES>(b, s_wave, tb);
-        if (s < nchunk) {
-            gt[s] = carry_a + xa;
-            eq[s] = carry_b + xb;
-        }
-        carry_a += ta;
-        carry_b += tb;
-    }
+    scan_array([&](uint32_t i) { return gt[i]; }, gt, nchunk, s_wave);
+    scan_array([&](uint32_t i) { return eq[i]; }, eq, nchunk, s_wave);
 }
 
 __global__ __launch_bounds__(BLOCK) void k_emit(Workspace ws, uint32_t L, uint32_t *out_idx, uint32_t *out_val) {
@@ -1543,7 +1525,8 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
     if (tot.seg_base) {
         // fixed grids: the number of chunks is known on the device only (<= the segments)
         const uint32_t tail_blocks = (uint32_t)std::min<uint64_t>(TAIL_BLOCKS, (tot.seg_base + WAVES - 1) / WAVES);
-        LAUNCH(ADACOMP_KERNEL_WORK, k_work, 1, ws, L);
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_WORK, k_work, dim3(1), dim3(CBLOCK), s, ws, L);
+        if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
         LAUNCH(ADACOMP_KERNEL_HIST, k_hist<0>, tail_blocks, ws, L);
         LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<0>, L, ws);
         LAUNCH(ADACOMP_KERNEL_HIST, k_hist<1>, tail_blocks, ws, L);
@@ -1551,7 +1534,8 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
         LAUNCH(ADACOMP_KERNEL_HIST, k_hist<2>, tail_blocks, ws, L);
         LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<2>, L, ws);
         LAUNCH(ADACOMP_KERNEL_COUNT_SEG, k_count, tail_blocks, ws, L);
-        LAUNCH(ADACOMP_KERNEL_SCAN, k_scan, L, ws);
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_SCAN, k_scan, dim3(L), dim3(CBLOCK), s, ws);
+        if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
         LAUNCH(ADACOMP_KERNEL_EMIT, k_emit, tail_blocks, ws, L, out_idx, out_val);
     }
     LAUNCH(ADACOMP_KERNEL_IDENTITY, k_identity, tot.iblk_base, ws, L, out_idx, out_val);
