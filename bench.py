@@ -73,6 +73,8 @@ def main():
                          "211,690-parameter network and 200 workers of the paper's experiments (latency regime); "
                          "cnn_apply, mid: the small and the mid-size CNN configurations")
     ap.add_argument("--rate", type=float, default=None, help="compression ratio c (default: the workload's first)")
+    ap.add_argument("--rows-shared", action="store_true",
+                    help="with --row-spread: the same rows are large in every worker's gradient")
     ap.add_argument("--row-spread", type=float, default=0.0,
                     help="scale every row of 1024 consecutive gradient elements by exp(s * N(0,1)): large entries "
                          "cluster in rows as in real weight gradients (default 0: the independent entries of the "
@@ -105,7 +107,7 @@ def main():
     L, N = len(sizes), sum(sizes)
     pulls = workloads.pull_timestamps(workloads.staleness(cfg))
 
-    grads = [workloads.gradient(cfg, q, device=dev, row_spread=args.row_spread) for q in range(Q)]      # 16 x 4 GB resident
+    grads = [workloads.gradient(cfg, q, device=dev, row_spread=args.row_spread, rows_shared=args.rows_shared) for q in range(Q)]      # 16 x 4 GB resident
     theta = workloads.theta0(cfg, device=dev)
     state = ac.State(theta)
     cap = sum(ac.adacomp_count(n, rate) for n in sizes)
@@ -240,7 +242,7 @@ def main():
                     "1 apply of the queue"),
                    "select_calls_per_step": 1 if batched else Q, "select_streams": ns, "hip_graph": bool(args.graph),
                    "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q,
-                   "row_spread": args.row_spread},
+                   "row_spread": args.row_spread, "rows_shared": bool(args.rows_shared)},
         "roofline": {"bound": "hbm", "kernel": "k_small" if small else "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": 1e3 * f_avg_s,

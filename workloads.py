@@ -135,11 +135,13 @@ _DISTS = {"heavy_tail": heavy_tail, "laplace": laplace, "mixture": mixture,
 ROW = 1024  # elements per row of the row-scaled variant
 
 
-def gradient_layer(cfg, update, layer, n=None, device="cpu", row_spread=0.0):
+def gradient_layer(cfg, update, layer, n=None, device="cpu", row_spread=0.0, rows_shared=False):
     """Tensor `layer` of the gradient pushed by the worker of queue slot `update`.  With
     row_spread s > 0 every row of ROW consecutive elements is scaled by exp(s * N(0,1)): large
     entries then cluster in some rows, as they do in the gradient of a weight matrix (an outer
-    product of a layer's inputs and its output deltas), instead of being spread evenly."""
+    product of a layer's inputs and its output deltas), instead of being spread evenly.  With
+    rows_shared the scales of a tensor are the same for every worker (the same rows are hot in
+    all queued updates), else each worker draws its own."""
     c = CONFIGS[cfg]
     if n is None:
         n = sizes_of(cfg)[layer]
@@ -147,15 +149,16 @@ def gradient_layer(cfg, update, layer, n=None, device="cpu", row_spread=0.0):
     x = _DISTS[c["dist"]](n, gen, device)
     if row_spread > 0.0 and n > 0:
         rows = (n + ROW - 1) // ROW
-        scale = torch.exp(row_spread * torch.randn(rows, generator=gen, device=device, dtype=torch.float32))
+        gen_rows = _gen(device, c["seed"], 0, layer, 4242) if rows_shared else gen
+        scale = torch.exp(row_spread * torch.randn(rows, generator=gen_rows, device=device, dtype=torch.float32))
         x = x * scale.repeat_interleave(ROW)[:n]
     return x
 
 
-def gradient(cfg, update=0, device="cpu", layers=None, row_spread=0.0):
+def gradient(cfg, update=0, device="cpu", layers=None, row_spread=0.0, rows_shared=False):
     sizes = sizes_of(cfg)
     sel = range(len(sizes)) if layers is None else layers
-    return [gradient_layer(cfg, update, l, sizes[l], device, row_spread) for l in sel]
+    return [gradient_layer(cfg, update, l, sizes[l], device, row_spread, rows_shared) for l in sel]
 
 
 def theta0(cfg, device="cpu", layers=None):
