@@ -670,3 +670,36 @@ def test_dense_queues_one_thread_per_coordinate(ac, dev, monkeypatch, Q, density
         a = Q // 3
         got, _, st = run_gpu(ac, theta0, ups, pulls, 0.03, dev, chunks=[a, 1, Q - a - 1], history=Q)
         assert compare(got, want, f"{kernel}: Q={Q} density={density}, three calls with a trace") == 0
+
+
+@pytest.mark.parametrize("Q", [10, 64, 70])
+def test_tiles_that_every_update_fills(ac, dev, monkeypatch, Q):
+    """A sparse queue (large tiles) in which every update also carries one whole stretch of 3000
+    consecutive parameters, as when the same rows are large in every worker's gradient: those tiles
+    hold thousands of queued entries, slices of up to 2048 entries per update, and are replayed by
+    the kernels for tiles that the sort declines (out of LDS up to 64 updates, from global memory
+    beyond), in one call and in calls with a trace."""
+    monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
+    monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", "tiled")
+    rng = np.random.default_rng(500 + Q)
+    sizes = [2048 * 12 + 77, 9]
+    ups = random_updates(rng, sizes, Q, 0.002, zero_frac=0.1)
+    hot = np.arange(5000, 8000, dtype=np.uint32)
+    for q in range(Q):
+        off, idx, val = ups[q]
+        a, b = int(off[0]), int(off[1])
+        merged = np.union1d(idx[a:b], hot).astype(np.uint32)
+        v = rng.standard_normal(merged.size).astype(np.float32)
+        v[rng.random(merged.size) < 0.05] = 0.0
+        shift = merged.size - (b - a)
+        ups[q] = (np.concatenate([off[:1], off[1:] + shift]).astype(np.uint64),
+                  np.concatenate([merged, idx[b:]]), np.concatenate([v, val[b:]]))
+    pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    want = run_oracle(theta0, ups, pulls, 0.02)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev)
+    assert st.t == Q
+    assert compare(got, want, f"filled tiles, Q={Q}, one call") == 0
+    a = Q // 3
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev, chunks=[a, 2, Q - a - 2], history=Q)
+    assert compare(got, want, f"filled tiles, Q={Q}, three calls with a trace") == 0
