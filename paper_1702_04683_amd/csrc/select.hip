@@ -854,6 +854,7 @@ __device__ __forceinline__ void small_find_bin(const uint32_t *s_hist, uint32_t 
 }
 
 constexpr uint32_t SCAND = 448;  // candidate slots per wave of k_small (16 waves: 56 KB of LDS)
+constexpr uint32_t TINY_MAX = 512;            // largest tensor k_small ranks by all-pairs comparison (at most SBLOCK, and BINS / 2)
 constexpr uint32_t SMALL_SAMPLE_MIN = 32768;  // smallest tensor k_small samples before reading it whole
 
 // Digit of `key` at a level of the descent, if the bits above the digit equal `prefix`.
@@ -920,7 +921,7 @@ __device__ __forceinline__ void small_hist_global(const SmallDesc &d, bool vec, 
 // does), which usually replaces the level-0 pass over the whole tensor by one over an eighth.
 __global__ __launch_bounds__(SBLOCK) void k_small(const SmallEntry *S, const uint64_t *layer_off, uint32_t *out_idx,
                                                   uint32_t *out_val) {
-    __shared__ uint32_t s_hist[BINS];
+    __shared__ __align__(8) uint32_t s_hist[BINS];  // also used as 64-bit words by the all-pairs path
     __shared__ uint32_t s_cidx[SWAVES][SCAND];
     __shared__ uint32_t s_cval[SWAVES][SCAND];
     __shared__ uint32_t s_wave[SWAVES];
@@ -933,6 +934,33 @@ __global__ __launch_bounds__(SBLOCK) void k_small(const SmallEntry *S, const uin
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wv = tid / WAVE;
     const bool vec = ((uintptr_t)d.g & 15u) == 0;
     const uint32_t nquads = (d.n + 3) / 4;
+
+    // A tensor of a few hundred elements (a bias vector, a small convolution kernel) needs none of
+    // the machinery below: one element per thread, its rank in the order of the selection (larger
+    // key first, lower index first among equal keys) by comparison with every other element, and
+    // the selected ones written at the number of selected elements before them.
+    if (d.n <= TINY_MAX) {
+        uint64_t *s_order = reinterpret_cast<uint64_t *>(s_hist);  // key << 32 | ~index: greater = earlier in the order
+        uint32_t bits = 0;
+        uint64_t mine = 0;
+        if (tid < d.n) {
+            bits = reinterpret_cast<const uint32_t *>(d.g)[tid];
+            mine = ((uint64_t)mag_key(bits) << 32) | (uint32_t)~tid;
+            s_order[tid] = mine;
+        }
+        __syncthreads();
+        uint32_t rank = 0;
+        if (tid < d.n)
+            for (uint32_t j = 0; j < d.n; ++j) rank += s_order[j] > mine ? 1u : 0u;
+        const bool selected = tid < d.n && rank < d.k;
+        uint32_t total;
+        const uint32_t before = block_exclusive_scan<SWAVES>(selected ? 1u : 0u, s_wave, total);
+        if (selected) {
+            out_idx[d.out_off + before] = tid;
+            out_val[d.out_off + before] = bits;
+        }
+        return;
+    }
 
     // Ordered compaction of the entries whose key lies in bin `bin_lo` (of level 0) or above, wave
     // by wave over contiguous shares, into the waves' LDS slots.  False if a wave ran out of slots.

@@ -302,11 +302,11 @@ def test_random_shapes_rates_and_counts(ac, dev, seed):
 @pytest.mark.parametrize("small", ["0", "1"])
 def test_sizes_around_every_internal_boundary(ac, dev, monkeypatch, small):
     """Tensor sizes at and next to the sizes the kernels are built around (4-element loads, 256-element
-    pieces, 8192-element wave segments, 2048-candidate chunks, the 2^18 limit of the one-workgroup
-    path), each with k = 1, k = n - 1 and two rates, through the pipeline and through the one-workgroup path."""
+    pieces, the 512 elements up to which a tensor is ranked by all-pairs comparison, 8192-element wave
+    segments, 2048-candidate chunks, the 2^18 limit of the one-workgroup path), each with k = 1, k = n - 1 and two rates, through the pipeline and through the one-workgroup path."""
     monkeypatch.setenv("ADACOMP_SELECT_SMALL", small)
     gen = torch.Generator(device=dev).manual_seed(77)
-    sizes = [1, 2, 3, 4, 5, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049, 8191, 8192, 8193, 16383, 16384, 16385,
+    sizes = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 2047, 2048, 2049, 8191, 8192, 8193, 16383, 16384, 16385,
              65535, 65537, 262143, 262144, 262145, 262144 + 8192, 524287, 524288, 524289]
     tensors = [(torch.randn(n, generator=gen, device=dev) * 7).round() / 7 for n in sizes]    # ties are common
     for rate in (0.01, 0.2):
@@ -377,3 +377,22 @@ def test_sample_that_misjudges_the_threshold(ac, dev, bias, what):
     check(ac, [g], 0.005, what=what)
     rows = workloads.gradient("mid", 3, device=dev, layers=[5, 6], row_spread=1.5)
     check(ac, rows, 0.005, what="row-scaled gradient")
+
+
+def test_tiny_tensors_special_values_and_ties(ac, dev):
+    """Tensors of at most 512 elements are ranked by all-pairs comparison in one workgroup: ties
+    (lower index first), signed zeros, denormals, infinities and NaNs with payloads must come
+    out as the oracle orders them, at every count from 0 to n."""
+    gen = torch.Generator(device=dev).manual_seed(123)
+    n = 300
+    x = (torch.randn(n, generator=gen, device=dev) * 3).round() / 3          # many equal magnitudes, +x and -x
+    bits = x.view(torch.int32).clone()
+    bits[5] = 0x7FC00001; bits[6] = -0x00400000 + 7; bits[7] = 0x7F800000; bits[8] = -0x00800000   # NaNs, +inf, -inf
+    bits[9] = 1; bits[10] = -0x7FFFFFFF; bits[11] = 0; bits[12] = -0x80000000                     # denormals, +0, -0
+    special = bits.view(torch.float32).contiguous()
+    zeros = torch.zeros(37, device=dev)
+    zeros[::2] = -0.0
+    one = torch.tensor([-2.5], device=dev)
+    for k in (0, 1, 2, 13, 150, 299, 300):
+        check(ac, [special, zeros, one, x[:64].contiguous(), x[:65].contiguous()], 0.5,
+              k_override=[k, min(k, 37), min(k, 1), min(k, 64), min(k, 65)], what=f"tiny tensors, k = {k}")
