@@ -9,8 +9,9 @@
 //
 // One wave owns one block in every kernel: the gaps come from a lane shuffle, the width from
 // a wave-wide OR, the packed bits are assembled in LDS and leave as whole words.  Where a
-// block's words start depends on the widths of all earlier blocks: a single-workgroup scan
-// between the two passes.  The unpacker trusts nothing in the stream: every read is bounded
+// block's words start depends on the widths of all earlier blocks: the first pass leaves
+// every block's offset inside its group of 16 blocks and the group's total, a single-workgroup
+// scan over the group totals sits between the two passes.  The unpacker trusts nothing in the stream: every read is bounded
 // by the stream length the host states and every write by the counts the host expects.
 #include <algorithm>
 #include <vector>
@@ -26,12 +27,14 @@ constexpr uint32_t SCAN_BLOCK = 1024;
 constexpr uint32_t SCAN_ITEMS = 4;   // consecutive counts per thread and stretch of the single-workgroup scan
 constexpr uint32_t SCAN_SUB = 4;     // stretches per round
 constexpr uint32_t MAGIC = 0x31434441u;
+constexpr uint32_t SUPER = 16;       // blocks per group of the two-level scan (one 1024-thread workgroup of the packer)
 
 struct Wire {
     const uint64_t *off;      // layer_off_dev of the update [L+1]
     const uint32_t *blk_base; // [L+1] first block of every tensor
-    uint32_t *nw;             // [B+1] delta words per block, then their exclusive scan; nw[B] = sum
-    uint32_t L, B;
+    uint32_t *nw;             // [B] delta words of the earlier blocks of the same group
+    uint32_t *ng;             // [G+1] delta words per group of SUPER blocks, then their exclusive scan; ng[G] = sum
+    uint32_t L, B, G;
     uint64_t total;           // entries
     uint64_t first_at, width_at, delta_at;  // word positions in the stream
 };
@@ -63,40 +66,55 @@ __device__ __forceinline__ uint32_t gap_of(uint32_t mine, uint32_t lane, uint32_
 
 __device__ __forceinline__ uint32_t bit_length(uint32_t x) { return x ? 32u - (uint32_t)__clz((int)x) : 0u; }
 
-// pass 1 of the packer: first index, width and word count of every block
-__global__ __launch_bounds__(BLOCK) void k_wire_measure(Wire w, const uint32_t *idx, uint32_t *out, uint64_t cap) {
-    const uint32_t lane = threadIdx.x & (WAVE - 1);
-    const uint32_t b = blockIdx.x * WAVES + threadIdx.x / WAVE;
-    if (b >= w.B) return;
-    uint32_t l, m;
-    uint64_t e0;
-    locate(w, b, l, e0, m);
-    const uint32_t mine = lane < m ? idx[e0 + lane] : 0u;
-    // OR of the gaps has the bit length of the largest gap
-    const uint32_t width = bit_length(wave_or(gap_of(mine, lane, m)));
+// pass 1 of the packer: first index and width of every block; its word count as an offset inside
+// its group (one workgroup = one group of SUPER blocks) and the group's total
+__global__ __launch_bounds__(SUPER * WAVE) void k_wire_measure(Wire w, const uint32_t *idx, uint32_t *out, uint64_t cap) {
+    __shared__ uint32_t s_n[SUPER];
+    const uint32_t lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
+    const uint32_t b = blockIdx.x * SUPER + wv;
+    uint32_t count = 0;
+    if (b < w.B) {
+        uint32_t l, m;
+        uint64_t e0;
+        locate(w, b, l, e0, m);
+        const uint32_t mine = lane < m ? idx[e0 + lane] : 0u;
+        // OR of the gaps has the bit length of the largest gap
+        const uint32_t width = bit_length(wave_or(gap_of(mine, lane, m)));
+        count = ((m - 1) * width + 31u) >> 5;
+        if (lane == 0) {
+            if (w.first_at + b < cap) out[w.first_at + b] = mine;
+            const uint64_t byte = w.width_at * 4 + b;
+            if (byte < cap * 4) reinterpret_cast<uint8_t *>(out)[byte] = (uint8_t)width;
+            if (b == w.B - 1)  // zero padding of the width bytes
+                for (uint64_t p = byte + 1; p < w.delta_at * 4 && p < cap * 4; ++p) reinterpret_cast<uint8_t *>(out)[p] = 0;
+        }
+    }
+    if (lane == 0) s_n[wv] = count;
+    __syncthreads();
     if (lane == 0) {
-        w.nw[b] = ((m - 1) * width + 31u) >> 5;
-        if (w.first_at + b < cap) out[w.first_at + b] = mine;
-        const uint64_t byte = w.width_at * 4 + b;
-        if (byte < cap * 4) reinterpret_cast<uint8_t *>(out)[byte] = (uint8_t)width;
-        if (b == w.B - 1)  // zero padding of the width bytes
-            for (uint64_t p = byte + 1; p < w.delta_at * 4 && p < cap * 4; ++p) reinterpret_cast<uint8_t *>(out)[p] = 0;
+        uint32_t before = 0, all = 0;
+        for (uint32_t i = 0; i < SUPER; ++i) {
+            if (i < wv) before += s_n[i];
+            all += s_n[i];
+        }
+        if (b < w.B) w.nw[b] = before;
+        if (wv == 0) w.ng[blockIdx.x] = all;
     }
 }
 
-// nw[0..B) -> exclusive prefix sums, nw[B] = sum.  One workgroup.  A round covers SCAN_SUB
+// ng[0..G) -> exclusive prefix sums, ng[G] = sum.  One workgroup.  A round covers SCAN_SUB
 // stretches of SCAN_BLOCK * SCAN_ITEMS counts; their loads are issued together, so that the
 // memory latency is paid once per round and not once per stretch.
 __device__ __forceinline__ void scan_words(const Wire &w, uint32_t *s_wave) {
     constexpr uint32_t STRETCH = SCAN_BLOCK * SCAN_ITEMS;
     uint32_t carry = 0;
-    for (uint32_t base = 0; base < w.B; base += STRETCH * SCAN_SUB) {
+    for (uint32_t base = 0; base < w.G; base += STRETCH * SCAN_SUB) {
         uint32_t v[SCAN_SUB][SCAN_ITEMS];
 #pragma unroll
         for (uint32_t u = 0; u < SCAN_SUB; ++u) {
             const uint32_t i0 = base + u * STRETCH + threadIdx.x * SCAN_ITEMS;
 #pragma unroll
-            for (uint32_t j = 0; j < SCAN_ITEMS; ++j) v[u][j] = i0 + j < w.B ? w.nw[i0 + j] : 0u;
+            for (uint32_t j = 0; j < SCAN_ITEMS; ++j) v[u][j] = i0 + j < w.G ? w.ng[i0 + j] : 0u;
         }
 #pragma unroll
         for (uint32_t u = 0; u < SCAN_SUB; ++u) {
@@ -108,13 +126,13 @@ __device__ __forceinline__ void scan_words(const Wire &w, uint32_t *s_wave) {
             uint32_t run = carry + block_exclusive_scan<SCAN_BLOCK / WAVE>(sum, s_wave, all);
 #pragma unroll
             for (uint32_t j = 0; j < SCAN_ITEMS; ++j) {
-                if (i0 + j < w.B) w.nw[i0 + j] = run;
+                if (i0 + j < w.G) w.ng[i0 + j] = run;
                 run += v[u][j];
             }
             carry += all;
         }
     }
-    if (threadIdx.x == 0) w.nw[w.B] = carry;
+    if (threadIdx.x == 0) w.ng[w.G] = carry;
 }
 
 // packer: offsets of the blocks' words, the header, and the length of the stream
@@ -122,7 +140,7 @@ __global__ __launch_bounds__(SCAN_BLOCK) void k_wire_scan_pack(Wire w, uint32_t 
     __shared__ uint32_t s_wave[SCAN_BLOCK / WAVE];
     scan_words(w, s_wave);
     __syncthreads();
-    if (threadIdx.x == 0) *words_out = w.delta_at + w.nw[w.B] + w.total;
+    if (threadIdx.x == 0) *words_out = w.delta_at + w.ng[w.G] + w.total;
     if (4 + (uint64_t)w.L > cap) return;
     if (threadIdx.x == 0) {
         out[0] = MAGIC;
@@ -155,29 +173,40 @@ __global__ __launch_bounds__(BLOCK) void k_wire_write(Wire w, const uint32_t *id
         if (sh + width > 32) atomicOr(&s_bits[wv][at + 1], gap >> (32 - sh));
     }
     __builtin_amdgcn_wave_barrier();
-    const uint64_t pos = w.delta_at + w.nw[b];
+    const uint64_t pos = w.delta_at + w.ng[b / SUPER] + w.nw[b];
     if (lane < nwords && pos + lane < cap) out[pos + lane] = s_bits[wv][lane];
-    const uint64_t vpos = w.delta_at + w.nw[w.B] + e0 + lane;
+    const uint64_t vpos = w.delta_at + w.ng[w.G] + e0 + lane;
     if (lane < m && vpos < cap) out[vpos] = val[e0 + lane];
 }
 
 // flags of the unpacker
 enum : uint32_t { BAD_HEADER = 1, BAD_WIDTH = 2, BAD_LENGTH = 4, BAD_INDEX = 8 };
 
-// unpacker, pass 1: word count of every block from its width byte
+// unpacker, pass 1: word count of every block from its width byte, as an offset inside its
+// group of SUPER blocks (16 neighbouring lanes), and the group's total
 __global__ __launch_bounds__(BLOCK) void k_wire_widths(Wire w, const uint32_t *in, uint64_t nwords, uint32_t *flags) {
     const uint32_t b = blockIdx.x * BLOCK + threadIdx.x;
-    if (b >= w.B) return;
-    uint32_t l, m;
-    uint64_t e0;
-    locate(w, b, l, e0, m);
-    const uint64_t byte = w.width_at * 4 + b;
-    uint32_t width = byte < nwords * 4 ? reinterpret_cast<const uint8_t *>(in)[byte] : 0u;
-    if (width > 32) {
-        atomicOr(flags, (uint32_t)BAD_WIDTH);
-        width = 32;
+    uint32_t count = 0;
+    if (b < w.B) {
+        uint32_t l, m;
+        uint64_t e0;
+        locate(w, b, l, e0, m);
+        const uint64_t byte = w.width_at * 4 + b;
+        uint32_t width = byte < nwords * 4 ? reinterpret_cast<const uint8_t *>(in)[byte] : 0u;
+        if (width > 32) {
+            atomicOr(flags, (uint32_t)BAD_WIDTH);
+            width = 32;
+        }
+        count = ((m - 1) * width + 31u) >> 5;
     }
-    w.nw[b] = ((m - 1) * width + 31u) >> 5;
+    uint32_t incl = count;
+#pragma unroll
+    for (uint32_t d = 1; d < SUPER; d <<= 1) {
+        const uint32_t y = __shfl_up(incl, d, SUPER);
+        if ((threadIdx.x & (SUPER - 1)) >= d) incl += y;
+    }
+    if (b < w.B) w.nw[b] = incl - count;
+    if ((b & (SUPER - 1)) == SUPER - 1 && b / SUPER < w.G) w.ng[b / SUPER] = incl;
 }
 
 // unpacker: offsets of the blocks' words; header and stream length against what the host expects
@@ -190,7 +219,7 @@ __global__ __launch_bounds__(SCAN_BLOCK) void k_wire_scan_unpack(Wire w, const u
     if (threadIdx.x == 0) {
         if (nwords < 4 || in[0] != MAGIC || in[1] != w.L || in[2] != (uint32_t)w.total || in[3] != (uint32_t)(w.total >> 32))
             bad |= BAD_HEADER;
-        if (w.delta_at + w.nw[w.B] + w.total != nwords) bad |= BAD_LENGTH;
+        if (w.delta_at + w.ng[w.G] + w.total != nwords) bad |= BAD_LENGTH;
     }
     for (uint32_t l = threadIdx.x; l < w.L; l += SCAN_BLOCK)
         if (4 + (uint64_t)l >= nwords || in[4 + l] != (uint32_t)(w.off[l + 1] - w.off[l])) bad |= BAD_HEADER;
@@ -209,7 +238,7 @@ __global__ __launch_bounds__(BLOCK) void k_wire_read(Wire w, const uint32_t *in,
     const uint64_t byte = w.width_at * 4 + b;
     uint32_t width = byte < nwords * 4 ? reinterpret_cast<const uint8_t *>(in)[byte] : 0u;
     if (width > 32) width = 32;
-    const uint64_t pos = w.delta_at + w.nw[b];
+    const uint64_t pos = w.delta_at + w.ng[b / SUPER] + w.nw[b];
     unsigned long long step = 0;  // distance to the previous entry
     if (lane >= 1 && lane < m) {
         uint32_t gap = 0;
@@ -231,7 +260,7 @@ __global__ __launch_bounds__(BLOCK) void k_wire_read(Wire w, const uint32_t *in,
     if (lane < m) {
         if (step > 0xffffffffull) atomicOr(flags, (uint32_t)BAD_INDEX);
         idx[e0 + lane] = (uint32_t)step;
-        const uint64_t vpos = w.delta_at + w.nw[w.B] + e0 + lane;
+        const uint64_t vpos = w.delta_at + w.ng[w.G] + e0 + lane;
         val[e0 + lane] = vpos < nwords ? in[vpos] : 0u;
     }
 }
@@ -239,7 +268,8 @@ __global__ __launch_bounds__(BLOCK) void k_wire_read(Wire w, const uint32_t *in,
 struct WirePlan {
     std::vector<uint32_t> blk_base;
     uint64_t B = 0, total = 0, first_at = 0, width_at = 0, delta_at = 0;
-    size_t blk_base_at = 0, nw_at = 0, bytes = 0;
+    size_t blk_base_at = 0, nw_at = 0, ng_at = 0, bytes = 0;
+    uint64_t G = 0;
 };
 
 int make_wire_plan(const uint64_t *layer_off, uint32_t L, WirePlan &p) {
@@ -262,8 +292,10 @@ int make_wire_plan(const uint64_t *layer_off, uint32_t L, WirePlan &p) {
     p.width_at = p.first_at + B;
     p.delta_at = p.width_at + (B + 3) / 4;
     p.blk_base_at = 0;
+    p.G = (B + SUPER - 1) / SUPER;
     p.nw_at = align_up(((size_t)L + 1) * sizeof(uint32_t), 256);
-    p.bytes = p.nw_at + align_up(((size_t)B + 1) * sizeof(uint32_t), 256);
+    p.ng_at = p.nw_at + align_up(((size_t)B + 1) * sizeof(uint32_t), 256);
+    p.bytes = p.ng_at + align_up(((size_t)p.G + 1) * sizeof(uint32_t), 256);
     return ADACOMP_OK;
 }
 
@@ -272,8 +304,10 @@ Wire device_view(const WirePlan &p, uint32_t L, const uint64_t *off_dev, char *w
     w.off = off_dev;
     w.blk_base = reinterpret_cast<const uint32_t *>(wsb + p.blk_base_at);
     w.nw = reinterpret_cast<uint32_t *>(wsb + p.nw_at);
+    w.ng = reinterpret_cast<uint32_t *>(wsb + p.ng_at);
     w.L = L;
     w.B = (uint32_t)p.B;
+    w.G = (uint32_t)p.G;
     w.total = p.total;
     w.first_at = p.first_at;
     w.width_at = p.width_at;
@@ -335,8 +369,8 @@ extern "C" int adacomp_wire_pack(const adacomp_update_t *update, uint32_t *wire,
         return ADACOMP_ERR_HIP;
     const unsigned grid = (unsigned)((p.B + WAVES - 1) / WAVES);
     if (p.B) {
-        ADACOMP_LAUNCH(ADACOMP_KERNEL_WIRE_MEASURE, k_wire_measure, dim3(grid), dim3(BLOCK), s, w, update->idx, wire,
-                       wire_cap);
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_WIRE_MEASURE, k_wire_measure, dim3((unsigned)p.G), dim3(SUPER * WAVE), s, w,
+                       update->idx, wire, wire_cap);
         CHECK_LAUNCH();
     }
     ADACOMP_LAUNCH(ADACOMP_KERNEL_WIRE_SCAN, k_wire_scan_pack, dim3(1), dim3(SCAN_BLOCK), s, w, wire, wire_cap,
