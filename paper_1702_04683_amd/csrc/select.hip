@@ -1518,19 +1518,18 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
     if (plan.out_total && (!out->idx || !out->val)) return ADACOMP_ERR_NULL;
     if (((uintptr_t)out->idx & 3u) || ((uintptr_t)out->val & 3u) || ((uintptr_t)out->layer_off_dev & 7u))
         return ADACOMP_ERR_ALIGNMENT;
-    const uint32_t n_tensors = L;
-    L = (uint32_t)plan.desc.size() - 1;  // from here on: the tensors of the pipeline
+    const uint32_t Lp = (uint32_t)plan.desc.size() - 1;  // the tensors of the pipeline (small and empty ones are not among them)
     Workspace ws;
-    carve(plan, L, workspace, ws);
+    carve(plan, Lp, workspace, ws);
     if (!workspace || ((uintptr_t)workspace & 255u) || ws_bytes < ws.bytes) return ADACOMP_ERR_WORKSPACE;
 
-    for (uint32_t l = 0; l <= n_tensors; ++l) out->layer_off[l] = plan.off[l];
+    for (uint32_t l = 0; l <= L; ++l) out->layer_off[l] = plan.off[l];
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (put_async(out->layer_off_dev, plan.off.data(), plan.off.size() * sizeof(uint64_t), s) != hipSuccess)
         return ADACOMP_ERR_HIP;
-    if (n_tensors == 0) return ADACOMP_OK;
-    const LayerDesc &tot = plan.desc[L];
+    if (L == 0) return ADACOMP_OK;
+    const LayerDesc &tot = plan.desc[Lp];
     uint32_t *out_idx = out->idx;
     uint32_t *out_val = reinterpret_cast<uint32_t *>(out->val);
     if (!plan.small.empty()) {
@@ -1544,40 +1543,40 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
     if (put_async(ws.desc, plan.desc.data(), plan.desc.size() * sizeof(LayerDesc), s) != hipSuccess)
         return ADACOMP_ERR_HIP;
     if (tot.seg_base) {
-        if (fill_u32_async(ws.hist, 0u, (size_t)L * BINS, s) != hipSuccess) return ADACOMP_ERR_HIP;
-        LAUNCH(ADACOMP_KERNEL_SAMPLE_HIST, k_sample_hist, tot.sblk_base, ws, L);
-        LAUNCH(ADACOMP_KERNEL_PICK, k_pick, L, ws);
+        if (fill_u32_async(ws.hist, 0u, (size_t)Lp * BINS, s) != hipSuccess) return ADACOMP_ERR_HIP;
+        LAUNCH(ADACOMP_KERNEL_SAMPLE_HIST, k_sample_hist, tot.sblk_base, ws, Lp);
+        LAUNCH(ADACOMP_KERNEL_PICK, k_pick, Lp, ws);
     }
     if (tot.sblk_base) {  // at least one tensor goes through the filter
         for (const Group &g : plan.groups) {
             if (!g.filters) continue;
             const uint32_t w0 = plan.desc[g.l0].wblk_base, g0 = plan.desc[g.l0].gblk_base;
-            LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, plan.desc[g.l1].wblk_base - w0, ws, L, w0);
+            LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, plan.desc[g.l1].wblk_base - w0, ws, Lp, w0);
             ADACOMP_LAUNCH(ADACOMP_KERNEL_CHECK, k_check, dim3(g.l1 - g.l0), dim3(CBLOCK), s, ws, g.l0);
             if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
             const uint32_t g_blocks = plan.desc[g.l1].gblk_base - g0;
-            if (plan.gsegs == GSEGS) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS>, g_blocks, ws, L, g0);
-            else if (plan.gsegs == GSEGS_MID) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_MID>, g_blocks, ws, L, g0);
-            else LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_FULL>, g_blocks, ws, L, g0);
+            if (plan.gsegs == GSEGS) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS>, g_blocks, ws, Lp, g0);
+            else if (plan.gsegs == GSEGS_MID) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_MID>, g_blocks, ws, Lp, g0);
+            else LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_FULL>, g_blocks, ws, Lp, g0);
         }
     }
     if (tot.seg_base) {
         // fixed grids: the number of chunks is known on the device only (<= the segments)
         const uint32_t tail_blocks = (uint32_t)std::min<uint64_t>(TAIL_BLOCKS, (tot.seg_base + WAVES - 1) / WAVES);
-        ADACOMP_LAUNCH(ADACOMP_KERNEL_WORK, k_work, dim3(1), dim3(CBLOCK), s, ws, L);
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_WORK, k_work, dim3(1), dim3(CBLOCK), s, ws, Lp);
         if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
-        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<0>, tail_blocks, ws, L);
-        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<0>, L, ws);
-        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<1>, tail_blocks, ws, L);
-        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<1>, L, ws);
-        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<2>, tail_blocks, ws, L);
-        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<2>, L, ws);
-        LAUNCH(ADACOMP_KERNEL_COUNT_SEG, k_count, tail_blocks, ws, L);
-        ADACOMP_LAUNCH(ADACOMP_KERNEL_SCAN, k_scan, dim3(L), dim3(CBLOCK), s, ws);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<0>, tail_blocks, ws, Lp);
+        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<0>, Lp, ws);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<1>, tail_blocks, ws, Lp);
+        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<1>, Lp, ws);
+        LAUNCH(ADACOMP_KERNEL_HIST, k_hist<2>, tail_blocks, ws, Lp);
+        LAUNCH(ADACOMP_KERNEL_RESOLVE, k_resolve<2>, Lp, ws);
+        LAUNCH(ADACOMP_KERNEL_COUNT_SEG, k_count, tail_blocks, ws, Lp);
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_SCAN, k_scan, dim3(Lp), dim3(CBLOCK), s, ws);
         if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
-        LAUNCH(ADACOMP_KERNEL_EMIT, k_emit, tail_blocks, ws, L, out_idx, out_val);
+        LAUNCH(ADACOMP_KERNEL_EMIT, k_emit, tail_blocks, ws, Lp, out_idx, out_val);
     }
-    LAUNCH(ADACOMP_KERNEL_IDENTITY, k_identity, tot.iblk_base, ws, L, out_idx, out_val);
+    LAUNCH(ADACOMP_KERNEL_IDENTITY, k_identity, tot.iblk_base, ws, Lp, out_idx, out_val);
     return ADACOMP_OK;
 }
 
