@@ -396,3 +396,24 @@ def test_tiny_tensors_special_values_and_ties(ac, dev):
     for k in (0, 1, 2, 13, 150, 299, 300):
         check(ac, [special, zeros, one, x[:64].contiguous(), x[:65].contiguous()], 0.5,
               k_override=[k, min(k, 37), min(k, 1), min(k, 64), min(k, 65)], what=f"tiny tensors, k = {k}")
+
+
+@pytest.mark.parametrize("group_mb", ["2", None])
+def test_row_scaled_gradients_in_many_groups(ac, dev, monkeypatch, group_mb):
+    """Tensors of 300K to 3M elements whose rows are scaled log-normally (large entries cluster),
+    in one call, with the candidate regions forced down to 2 MB (a dozen groups that reuse them)
+    and at their default size: regions that overflow, thresholds that fall short and tensors that
+    are read directly all occur side by side; every tensor must come out as the oracle orders it."""
+    if group_mb:
+        monkeypatch.setenv("ADACOMP_SELECT_GROUP_MB", group_mb)
+    gen = torch.Generator(device=dev).manual_seed(31)
+    rng = np.random.default_rng(31)
+    tensors = []
+    for i in range(10):
+        n = int(rng.integers(300_000, 3_000_000))
+        row = int(rng.choice([256, 1000, 4096]))
+        x = torch.randn(n, generator=gen, device=dev) * 1e-3
+        scale = torch.exp(float(rng.choice([0.7, 1.5, 2.5])) * torch.randn((n + row - 1) // row, generator=gen, device=dev))
+        tensors.append(x * scale.repeat_interleave(row)[:n])
+    for rate in (0.002, 0.02, 0.1):
+        check(ac, tensors, rate, what=f"row-scaled, groups of {group_mb} MB, rate {rate}")
