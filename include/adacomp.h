@@ -56,7 +56,9 @@ enum {
     ADACOMP_ERR_HISTORY = -9,         /* pull_ts precedes the oldest remembered update       */
     ADACOMP_ERR_LR = -10,             /* learning rate is not finite                         */
     ADACOMP_ERR_ALIGNMENT = -11,      /* a float/uint32 device pointer is not 4-byte aligned */
-    ADACOMP_ERR_HIP = -12             /* a HIP runtime call (kernel launch) failed           */
+    ADACOMP_ERR_HIP = -12,            /* a HIP runtime call (kernel launch) failed           */
+    ADACOMP_ERR_SCRATCH_LIMIT = -13   /* adacomp_select_noalloc: the call needs more scratch than
+                                         ADACOMP_SELECT_NOALLOC_SCRATCH_BYTES                */
 };
 
 /* One tensor of a worker's dense update Delta Theta^(w): a V_l or a beta_l
@@ -160,6 +162,22 @@ int adacomp_select_workspace(const uint64_t *n, uint32_t L, double rate,
 int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double rate,
                    const uint64_t *k_override, adacomp_update_t *out,
                    void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* adacomp_select for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, result and errors as adacomp_select, except that the scratch memory is a buffer of
+ * ADACOMP_SELECT_NOALLOC_SCRATCH_BYTES that is part of the library's device code: every GPU the
+ * library runs on holds one copy until the process ends.  The call allocates nothing on the
+ * device and frees nothing.  The device that hip_stream belongs to must be the current device.
+ * A call whose tensors need more scratch than that (adacomp_select_workspace() tells how much:
+ * about 3 MB for a 3.3M-parameter model at 1 %) is refused with ADACOMP_ERR_SCRATCH_LIMIT before
+ * anything is enqueued.  All calls on one GPU share that GPU's buffer, which keeps the previous
+ * call's contents (the kernels clear what they need cleared): calls on the same stream run one
+ * after the other and are safe, calls that overlap on one GPU (different streams, or threads
+ * with streams of their own) race. */
+#define ADACOMP_SELECT_NOALLOC_SCRATCH_BYTES (32u << 20)
+int adacomp_select_noalloc(const adacomp_layer_t *layers, uint32_t L, double rate,
+                           const uint64_t *k_override, adacomp_update_t *out, void *hip_stream);
 
 /* Bytes of DEVICE workspace adacomp_apply needs for a queue of Q updates (HOST array;
  * num_layers, layer_off and pull_ts are read) on L parameter tensors of sizes n[0..L)

@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     adacomp_count,
     adacomp_select_workspace,
     adacomp_select,
+    adacomp_select_noalloc,
+    SELECT_NOALLOC_SCRATCH_BYTES,
     adacomp_apply_workspace,
     adacomp_apply,
     adacomp_apply_global_staleness,

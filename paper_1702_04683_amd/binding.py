@@ -62,6 +62,8 @@ def load_library():
     lib.adacomp_select.restype = C.c_int
     lib.adacomp_select.argtypes = [C.POINTER(_Layer), u32, C.c_double, C.POINTER(u64), C.POINTER(_Update),
                                    vp, sz, vp]
+    lib.adacomp_select_noalloc.restype = C.c_int
+    lib.adacomp_select_noalloc.argtypes = [C.POINTER(_Layer), u32, C.c_double, C.POINTER(u64), C.POINTER(_Update), vp]
     lib.adacomp_apply_workspace.restype = C.c_int
     lib.adacomp_apply_workspace.argtypes = [C.POINTER(u64), u32, C.POINTER(_State), C.POINTER(_Update), u32,
                                             C.POINTER(sz)]
@@ -272,6 +274,22 @@ def adacomp_select(layers, rate, out, workspace, k_override=None, stream=None):
                                        _stream_ptr(stream, dev))
     if rc:
         raise AdaCompError(rc, "adacomp_select")
+    return out
+
+
+SELECT_NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def adacomp_select_noalloc(layers, rate, out, k_override=None, stream=None):
+    """SELECT_GRAD into `out` with the library's built-in scratch buffer instead of a workspace
+    (for callers that cannot allocate).  The tensors' device must be the current one.  Asynchronous."""
+    dev = out.idx.device
+    kov = _u64_array(k_override) if k_override is not None else None
+    cu = out.c_struct()
+    rc = load_library().adacomp_select_noalloc(_layers(layers), len(layers), float(rate), kov, C.byref(cu),
+                                               _stream_ptr(stream, dev))
+    if rc:
+        raise AdaCompError(rc, "adacomp_select_noalloc")
     return out
 
 

@@ -41,6 +41,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <cmath>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -1498,9 +1499,53 @@ extern "C" int adacomp_select_workspace(const uint64_t *n, uint32_t L, double ra
         }                                                                           \
     } while (0)
 
+// Scratch of adacomp_select_noalloc: one copy per GPU, held until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels are given the address that
+// call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[ADACOMP_SELECT_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES];  // device address of `scratch` on device d, once looked up
+
+// Address of `scratch` on the current device (looked up once per device).
+int scratch_of_current_device(void **ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return ADACOMP_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ADACOMP_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return ADACOMP_OK;
+}
+
+// static_scratch: the workspace is the library's own array; its address is looked up only once
+// the sizes are known to fit, and a call that needs more is refused with its own error code.
+int select_impl(const adacomp_layer_t *layers, uint32_t L, double rate, const uint64_t *k_override,
+                adacomp_update_t *out, void *workspace, size_t ws_bytes, bool static_scratch, void *hip_stream);
+
+}  // namespace
+
 extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double rate,
                               const uint64_t *k_override, adacomp_update_t *out,
                               void *workspace, size_t ws_bytes, void *hip_stream) {
+    return select_impl(layers, L, rate, k_override, out, workspace, ws_bytes, false, hip_stream);
+}
+
+extern "C" int adacomp_select_noalloc(const adacomp_layer_t *layers, uint32_t L, double rate,
+                                      const uint64_t *k_override, adacomp_update_t *out, void *hip_stream) {
+    return select_impl(layers, L, rate, k_override, out, nullptr, 0, true, hip_stream);
+}
+
+namespace {
+
+int select_impl(const adacomp_layer_t *layers, uint32_t L, double rate, const uint64_t *k_override,
+                adacomp_update_t *out, void *workspace, size_t ws_bytes, bool static_scratch, void *hip_stream) {
     if (!out || (L && !layers) || !out->layer_off || !out->layer_off_dev) return ADACOMP_ERR_NULL;
     if (out->num_layers != L) return ADACOMP_ERR_LAYER_MISMATCH;
     std::vector<uint64_t> n(L);
@@ -1520,6 +1565,13 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
         return ADACOMP_ERR_ALIGNMENT;
     const uint32_t Lp = (uint32_t)plan.desc.size() - 1;  // the tensors of the pipeline (small and empty ones are not among them)
     Workspace ws;
+    if (static_scratch) {
+        carve(plan, Lp, nullptr, ws);
+        if (ws.bytes > ADACOMP_SELECT_NOALLOC_SCRATCH_BYTES) return ADACOMP_ERR_SCRATCH_LIMIT;
+        rc = scratch_of_current_device(&workspace);
+        if (rc) return rc;
+        ws_bytes = ADACOMP_SELECT_NOALLOC_SCRATCH_BYTES;
+    }
     carve(plan, Lp, workspace, ws);
     if (!workspace || ((uintptr_t)workspace & 255u) || ws_bytes < ws.bytes) return ADACOMP_ERR_WORKSPACE;
 
@@ -1580,6 +1632,8 @@ extern "C" int adacomp_select(const adacomp_layer_t *layers, uint32_t L, double 
     return ADACOMP_OK;
 }
 
+}  // namespace
+
 extern "C" const char *adacomp_strerror(int code) {
     switch (code) {
         case ADACOMP_OK: return "success";
@@ -1595,6 +1649,7 @@ extern "C" const char *adacomp_strerror(int code) {
         case ADACOMP_ERR_LR: return "learning rate is not finite";
         case ADACOMP_ERR_ALIGNMENT: return "a device pointer is not aligned to its element size";
         case ADACOMP_ERR_HIP: return "a HIP runtime call failed";
+        case ADACOMP_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the library's built-in buffer holds";
         default: return "unknown adacomp error code";
     }
 }

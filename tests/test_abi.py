@@ -95,6 +95,21 @@ def test_select_argument_checks_run_before_any_launch(lib):
     assert lib.adacomp_select(layer, 1, 0.5, None, None, 0x10000, 1 << 30, None) == -1
 
 
+def test_select_noalloc_refuses_what_its_scratch_cannot_hold(lib):
+    """The size check is made on the host, before the built-in buffer is even looked up."""
+    sizes = [40_000_000]
+    assert ac.adacomp_select_workspace(sizes, 0.01) > ac.SELECT_NOALLOC_SCRATCH_BYTES
+    text = open(os.path.join(ROOT, "include", "adacomp.h")).read()
+    assert re.search(r"ADACOMP_SELECT_NOALLOC_SCRATCH_BYTES \((\d+)u << (\d+)\)", text).groups() == ("32", "20")
+    off = (C.c_uint64 * 2)()
+    layer = (binding._Layer * 1)()
+    layer[0].data, layer[0].n = 0x1000, sizes[0]
+    upd = binding._Update(1, C.cast(off, C.POINTER(C.c_uint64)), 0x2000, 0x3000, 0x4000, sizes[0], 0)
+    assert lib.adacomp_select_noalloc(layer, 1, 0.01, None, C.byref(upd), None) == -13
+    assert lib.adacomp_select_noalloc(layer, 1, 2.0, None, C.byref(upd), None) == -2
+    assert lib.adacomp_select_noalloc(layer, 1, 0.01, None, None, None) == -1
+
+
 def test_apply_argument_checks_run_before_any_launch(lib):
     off = (C.c_uint64 * 2)(0, 3)
     par = (binding._Layer * 1)()
