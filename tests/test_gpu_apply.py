@@ -54,6 +54,26 @@ def run_oracle(theta_host, updates_host, pulls, lr, method=oracle.HISTORY_LISTS,
     return theta
 
 
+def run_oracle_per_tensor(theta_host, updates_host, pulls, lr, method=oracle.HISTORY_LISTS, threads=16):
+    """The oracle's server, one instance per tensor, in parallel threads (the C call releases the
+    GIL).  Every instance sees the whole queue restricted to its tensor, so its timestamps are the
+    queue's; eqs. 3-5 couple nothing across parameters (pinned on the CPU by the oracle's
+    split-a-tensor test)."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    def one(l):
+        ups = []
+        for o, i, v in updates_host:
+            a, b = int(o[l]), int(o[l + 1])
+            ups.append((np.array([0, b - a], dtype=np.uint64), i[a:b], v[a:b]))
+        return run_oracle([theta_host[l]], ups, pulls, lr, method=method)[0]
+
+    order = sorted(range(len(theta_host)), key=lambda l: -theta_host[l].size)   # largest first
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        res = dict(zip(order, ex.map(one, order)))
+    return [res[l] for l in range(len(theta_host))]
+
+
 def compare(got, want, what):
     worst, differing = 0.0, 0
     for l, (a, b) in enumerate(zip(got, want)):
@@ -185,21 +205,24 @@ def test_cnn_apply_config(ac, dev):
 @pytest.mark.parametrize("rate", [0.001, 0.01, 0.1])
 def test_mid_apply_config(ac, dev, rate):
     """Config 'mid-size CNN' at 0.1%, 1% and 10% (at 10% every parameter is touched 6 times on
-    average: tiles of a few dozen parameters): 64 queued updates, staleness uniform in [1, 64].
-    The six tensors below 1M entries are checked in full against the oracle; the updates come
-    from the oracle's own selection."""
+    average): 64 queued updates, staleness uniform in [1, 64].  The whole model, all 8 tensors
+    including the 37.7M- and 16.8M-parameter ones, is checked entry by entry against the oracle;
+    the updates come from the oracle's own selection from the seeded gradients."""
     cfg = "mid"
-    layers = [0, 1, 2, 3, 4, 7]
+    sizes = workloads.sizes_of(cfg)
     Q, lr = 64, workloads.CONFIGS[cfg]["lr"]
     pulls = workloads.pull_timestamps(workloads.staleness(cfg))
-    grads = [[x.numpy() for x in workloads.gradient(cfg, q, layers=layers)] for q in range(Q)]
-    ups = oracle_select_parallel(grads, rate, threads=12)
-    theta0 = [t.numpy() for t in workloads.theta0(cfg, layers=layers)]
-    print(f"[apply] mid at {rate}: gpu", flush=True)
-    got, _, _ = run_gpu(ac, theta0, ups, pulls, lr, dev)
+    print(f"[apply] mid at {rate}: oracle selects 64 gradients of {sum(sizes)} entries", flush=True)
+    grads = [[x.cpu().numpy() for x in workloads.gradient(cfg, q, device=dev)] for q in range(Q)]
+    ups = oracle_select_parallel(grads, rate, threads=16)
+    del grads
+    theta0 = [t.numpy() for t in workloads.theta0(cfg)]
+    print(f"[apply] mid at {rate}: gpu, {int(ups[0][0][-1])} entries per update", flush=True)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, lr, dev)
+    assert st.t == Q
     print(f"[apply] mid at {rate}: oracle", flush=True)
-    want = run_oracle(theta0, ups, pulls, lr, method=oracle.HISTORY_BITMAP if rate > 0.05 else oracle.HISTORY_LISTS)
-    assert compare(got, want, f"mid apply at {rate}") == 0
+    want = run_oracle_per_tensor(theta0, ups, pulls, lr, method=oracle.HISTORY_BITMAP)
+    assert compare(got, want, f"mid apply at {rate}, whole model") == 0
 
 
 def test_extreme_staleness_long_queue(ac, dev):
@@ -225,18 +248,80 @@ def test_extreme_staleness_long_queue(ac, dev):
     assert max(int(c.max()) for c in cnt) > 3000      # this queue runs update by update: counters reach the thousands
 
 
+@pytest.mark.parametrize("plan", ["auto", "sweep"])
+def test_extreme_staleness_all_adversarial_tensors(ac, dev, plan, monkeypatch):
+    """The same 10,050-update queue (staleness 1 and 10^4 alternating) on all 40 adversarial tensors,
+    every update taking its one entry per tensor from a pool of up to 64 parameters spread over
+    the whole tensor, 5% of the values exact zeros.  Run as the library chooses and with the sweep
+    forced: there the general sorting kernel stages the queue 256 updates at a time in 40,000 tiles,
+    and the tiles of the small tensors, which collect up to 10,050 entries, go to the kernel that
+    replays a tile from global memory."""
+    if plan != "auto":
+        monkeypatch.setenv("ADACOMP_APPLY_PLAN", plan)
+    rng = np.random.default_rng(78)
+    sizes = workloads.sizes_of("adversarial")
+    assert len(sizes) == 40
+    Q = 10_050
+    pools = [np.sort(rng.choice(n, size=min(n, 64), replace=False)) for n in sizes]
+    ups = []
+    for q in range(Q):
+        idx = np.array([p[rng.integers(0, p.size)] for p in pools], dtype=np.uint32)
+        val = rng.standard_normal(len(sizes)).astype(np.float32)
+        val[rng.random(len(sizes)) < 0.05] = 0.0
+        ups.append((np.arange(len(sizes) + 1, dtype=np.uint64), idx, val))
+    stale = [1 if q % 2 else 10_000 for q in range(Q)]
+    pulls = workloads.pull_timestamps(stale)
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    print(f"[apply] long queue, 40 tensors, plan {plan}: gpu", flush=True)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.01, dev)
+    assert st.t == Q
+    print(f"[apply] long queue, 40 tensors, plan {plan}: oracle", flush=True)
+    want = run_oracle(theta0, ups, pulls, 0.01)
+    assert compare(got, want, f"long queue, 40 tensors, plan {plan}") == 0
+
+
+@pytest.mark.parametrize("Q", [300, 1000])
+def test_long_spread_queues_through_the_general_sweep(ac, dev, monkeypatch, Q):
+    """Queues longer than the kernels for short and dense queues take (more than 256 updates), with
+    the sweep forced: entries spread over ragged tensors of several tiles each, a stretch that every
+    update hits (its tile overflows and is replayed from global memory), zero-valued entries,
+    random pulls; in one call and in three calls with a trace."""
+    monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
+    rng = np.random.default_rng(600 + Q)
+    sizes = [2048 * 9 + 5, 1, 0, 50_001, 777]
+    ups = random_updates(rng, sizes, Q, 0.003, zero_frac=0.1)
+    hot = np.arange(30_000, 30_003, dtype=np.uint32)
+    for q in range(Q):
+        off, idx, val = ups[q]
+        a, b = int(off[3]), int(off[4])
+        merged = np.union1d(idx[a:b], hot).astype(np.uint32)
+        v = rng.standard_normal(merged.size).astype(np.float32)
+        shift = merged.size - (b - a)
+        ups[q] = (np.concatenate([off[:4], off[4:] + shift]).astype(np.uint64),
+                  np.concatenate([idx[:a], merged, idx[b:]]), np.concatenate([val[:a], v, val[b:]]))
+    pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    want = run_oracle(theta0, ups, pulls, 0.02)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev)
+    assert st.t == Q
+    assert compare(got, want, f"general sweep, Q={Q}, one call") == 0
+    a = Q // 3
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev, chunks=[a, 2, Q - a - 2], history=Q)
+    assert compare(got, want, f"general sweep, Q={Q}, three calls with a trace") == 0
+
+
 def test_flat_config_full_size_sampled(ac, dev):
     """The roofline configuration in the launch shapes bench.py times: 16 seeded 1B-element worker
     gradients (100 tensors of 10M each) go through ONE adacomp_select call over the 1600 tensors
     at 0.5%; its output is viewed as 16 updates (staleness uniform in [1, 16]) and applied by one
-    adacomp_apply call to 100 tensors of 10M parameters.  The oracle replays sampled tensors
-    (its own selection from the same bits, its own apply); properties that hold at any size are
+    adacomp_apply call to 100 tensors of 10M parameters.  The oracle replays ten tensors
+    chosen by seed (its own selection from the same bits, its own apply); properties that hold at any size are
     checked on many more."""
     cfg, rate = "flat", 0.005
     sizes = workloads.sizes_of(cfg)
     L, Q, lr = len(sizes), 16, workloads.CONFIGS[cfg]["lr"]
     pulls = workloads.pull_timestamps(workloads.staleness(cfg))
-    sample = [0, 41, 99]
+    sample = sorted(int(l) for l in np.random.default_rng(4004).choice(L, size=10, replace=False))
     theta = workloads.theta0(cfg, device=dev)
     theta0 = {l: theta[l].cpu().numpy().copy() for l in sample}
     print("[apply] flat: generating 16 gradients (64 GB)", flush=True)
@@ -278,14 +363,20 @@ def test_flat_config_full_size_sampled(ac, dev):
         assert bool(same[~touched].all()), f"tensor {l}: an unnamed parameter changed"
         assert float(same[touched].float().mean()) < 0.01, f"tensor {l}: named parameters did not move"
     del theta_before
-    print("[apply] flat: oracle on sampled tensors", flush=True)
+    print(f"[apply] flat: oracle on sampled tensors {sample}", flush=True)
+    jobs = [[host_g[l][q]] for l in sample for q in range(Q)]
+    sel = oracle_select_parallel(jobs, rate, threads=16)
+    del jobs, host_g
+    o_ups = {l: sel[n * Q:(n + 1) * Q] for n, l in enumerate(sample)}
     for l in sample:
-        o_ups = oracle_select_parallel([[x] for x in host_g[l]], rate, threads=8)
-        for q, (o, i, v) in enumerate(o_ups):       # the batched select against the oracle, entry by entry
+        for q, (o, i, v) in enumerate(o_ups[l]):    # the batched select against the oracle, entry by entry
             assert np.array_equal(ups[q].idx[l * k:(l + 1) * k].cpu().numpy().view(np.uint32), i), (q, l)
             assert np.array_equal(ups[q].val[l * k:(l + 1) * k].cpu().numpy().view(np.uint32), v.view(np.uint32))
-        want = run_oracle([theta0[l]], o_ups, pulls, lr)
-        assert compare([theta[l].cpu().numpy()], want, f"flat tensor {l}") == 0
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=10) as ex:
+        wants = list(ex.map(lambda l: run_oracle([theta0[l]], o_ups[l], pulls, lr)[0], sample))
+    for l, want in zip(sample, wants):
+        assert compare([theta[l].cpu().numpy()], [want], f"flat tensor {l}") == 0
 
 
 @pytest.mark.parametrize("plan", ["scatter", "sweep"])
