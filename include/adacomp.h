@@ -217,14 +217,15 @@ int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, adacomp_state
                   const adacomp_update_t *updates, uint32_t Q, float lr,
                   void *workspace, size_t ws_bytes, void *hip_stream);
 
-/* The same queue with the learning-rate rule the paper ascribes to its competitors, ASGD and
- * Comp-ASGD (Sec. 5.2: "the learning rate is divided by staleness and is global to each
- * update"): sigma = i - j for every entry of an update, alpha = lr / sigma if sigma != 0.
- * (Their selection, the largest entries across the whole model, is adacomp_select on the
- * model passed as one tensor.)  Arguments, checks and stream semantics as adacomp_apply;
- * no trace and no counters are needed: st->cnt and the history fields are neither read
- * nor written, any pull_ts <= apply time is accepted.  workspace: DEVICE, 256-byte aligned,
- * at least 32 * (L + 1) bytes rounded up to 256. */
+/* The same queue under the learning-rate rule that Sec. 5.2 describes for the competitors, ASGD
+ * and Comp-ASGD: one staleness per update, sigma = i - j for every entry of it, alpha = lr / sigma
+ * if sigma != 0.  (Their selection, the largest entries across the whole model, is
+ * adacomp_select on the model passed as one tensor.)  Arguments, checks and stream semantics as
+ * adacomp_apply; no counters are needed and st->cnt is neither read nor written; any
+ * pull_ts <= apply time is accepted.  With history_cap > 0 the applied updates are entered
+ * into the trace exactly as adacomp_apply enters them (same lifetime rule for their buffers), so
+ * the two calls can be mixed on one state.  workspace: DEVICE, 256-byte aligned, at least
+ * 32 * (L + 1) bytes rounded up to 256. */
 int adacomp_apply_global_staleness(const adacomp_param_layer_t *params, uint32_t L, adacomp_state_t *st,
                                    const adacomp_update_t *updates, uint32_t Q, float lr,
                                    void *workspace, size_t ws_bytes, void *hip_stream);
@@ -292,7 +293,8 @@ enum {
     ADACOMP_KERNEL_SAMPLE_HIST,    /* select: histogram of a strided sample                     */
     ADACOMP_KERNEL_PICK,           /* select: choose the filter threshold                       */
     ADACOMP_KERNEL_FILTER,         /* select: streaming read + ordered candidate compaction     */
-    ADACOMP_KERNEL_CHECK,          /* select: candidates sufficient?  offsets of their regions  */
+    ADACOMP_KERNEL_FINISH,         /* select: per tensor, threshold and ordered write straight from the
+                                      candidate regions; or the check that leaves it to the kernels below */
     ADACOMP_KERNEL_GATHER,         /* select: pack the candidate regions per tensor             */
     ADACOMP_KERNEL_WORK,           /* select: chunk numbering across tensors                    */
     ADACOMP_KERNEL_HIST,           /* select: radix-descent histogram (3 levels)                */

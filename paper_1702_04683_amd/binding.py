@@ -328,6 +328,7 @@ def adacomp_apply_global_staleness(params, state, updates, lr, workspace, stream
         workspace.numel() * workspace.element_size(), _stream_ptr(stream, dev))
     if rc:
         raise AdaCompError(rc, "adacomp_apply_global_staleness")
+    state._remember(state.t - len(updates), updates)
     return state
 
 

@@ -1363,6 +1363,7 @@ extern "C" int adacomp_apply_global_staleness(const adacomp_param_layer_t *param
                                               void *workspace, size_t ws_bytes, void *hip_stream) {
     if (!st || (L && !params)) return ADACOMP_ERR_NULL;
     if (st->num_layers != L) return ADACOMP_ERR_LAYER_MISMATCH;
+    if (st->history_cap && (!st->history || !st->history_off)) return ADACOMP_ERR_NULL;
     if (!std::isfinite(lr)) return ADACOMP_ERR_LR;
     int rc = check_updates(L, updates, Q);
     if (rc) return rc;
@@ -1391,6 +1392,13 @@ extern "C" int adacomp_apply_global_staleness(const adacomp_param_layer_t *param
     if (Q == 0) return ADACOMP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     ParamDesc *P = static_cast<ParamDesc *>(workspace);
+    bool any = false;
+    for (uint32_t q = 0; q < Q; ++q) any = any || updates[q].layer_off[L] > 0;
+    if (!any) {  // empty pushes only: nothing to enqueue
+        if (st->history_cap) remember(st, updates, Q, L, t0);
+        st->t = t0 + Q;
+        return ADACOMP_OK;
+    }
     if (put_async(P, table.data(), table.size() * sizeof(ParamDesc), s) != hipSuccess) return ADACOMP_ERR_HIP;
     for (uint32_t q = 0; q < Q; ++q) {
         const adacomp_update_t &u = updates[q];
@@ -1401,6 +1409,9 @@ extern "C" int adacomp_apply_global_staleness(const adacomp_param_layer_t *param
                        u.layer_off_dev, u.idx, u.val, total, lr, (uint32_t)(t0 + q - u.pull_ts));
         CHECK_LAUNCH();
     }
+    // the trace records which parameters an update touched, whichever rule set its step: a later
+    // adacomp_apply on this state may look back across these timestamps (eq. 3)
+    if (st->history_cap) remember(st, updates, Q, L, t0);
     st->t = t0 + Q;
     return ADACOMP_OK;
 }

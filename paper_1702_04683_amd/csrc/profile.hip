@@ -84,7 +84,7 @@ extern "C" const char *adacomp_kernel_name(int id) {
         case ADACOMP_KERNEL_SAMPLE_HIST: return "sample_hist";
         case ADACOMP_KERNEL_PICK: return "pick";
         case ADACOMP_KERNEL_FILTER: return "filter";
-        case ADACOMP_KERNEL_CHECK: return "check";
+        case ADACOMP_KERNEL_FINISH: return "finish";
         case ADACOMP_KERNEL_GATHER: return "gather";
         case ADACOMP_KERNEL_WORK: return "work";
         case ADACOMP_KERNEL_HIST: return "hist";

@@ -65,15 +65,26 @@ constexpr uint32_t SPIECES = 64;    // sampled pieces per sample-histogram workg
 constexpr uint32_t BLOCK = 256;     // threads per workgroup = 4 waves
 constexpr uint32_t WAVES = BLOCK / WAVE;
 constexpr uint32_t IDENT_TILE = BLOCK * 16;  // elements per identity-copy workgroup
-// Candidate regions of one group of tensors.  About a fifth of a region is written (its
-// capacity is three times the expected fill), so the lines a group really touches, ~80 MB, stay
-// in the 256 MB last-level cache until the gather has read them.  Measured on 16 x 4 GB
-// gradients: one group 14.7 ms per step, 384 MB groups 14.4, 192 MB 14.5+ (more launches), 768 MB erratic.
-constexpr uint64_t GROUP_BYTES = 384ull << 20;
 constexpr uint32_t SMALL_MAX = 1u << 18;     // largest tensor that one workgroup selects on its own
 constexpr uint64_t SMALL_TOTAL = 1ull << 26; // ... as long as all such tensors of the call hold no more elements than this
 constexpr uint32_t SBLOCK = 1024;            // threads of that workgroup
 constexpr uint32_t SWAVES = SBLOCK / WAVE;
+// k_finish: one workgroup takes a tensor from the candidates its filter left to its output
+constexpr uint32_t FUSE_MAX_SEG = 2048;      // most segments of such a tensor (16.7M elements)
+constexpr uint32_t FUSE_MAX_CAND = 1u << 17; // ... and most candidates the plan expects for it (the kernel accepts twice as many)
+constexpr uint32_t FUSE_SHIFT = 11;          // key bits resolved by its second histogram; the first takes the 12 above
+constexpr uint32_t FUSE_SB = 16;             // segments whose candidate loads a wave has in flight together
+
+// Candidate regions of one group of tensors: consecutive tensors are filtered and finished (or
+// checked and packed) together, and the next group reuses the same region memory.  About a fifth
+// of a region is written (its capacity is three times the expected fill), so the lines a group
+// really touches stay in the 256 MB last-level cache until they have been read, and are
+// overwritten there by the next group instead of travelling to HBM.  k_finish gives every tensor of
+// the group one workgroup: a group of more tensors than the chip has compute units takes two
+// rounds of them.  Measured on 16 x 4 GB gradients, filter launches per step: one group 11.3 ms,
+// 384 MB groups 10.6 ms, 768 MB groups 10.5 ms.
+constexpr uint64_t GROUP_BYTES = 768ull << 20;
+constexpr uint32_t GROUP_TENSORS = 256;
 
 enum : uint32_t { MODE_EMPTY = 0, MODE_IDENTITY = 1, MODE_FILTER = 2, MODE_DENSE = 3, MODE_SMALL = 4 };
 
@@ -111,7 +122,7 @@ struct LayerDesc {
     uint32_t wblk_base;  //   one segment per wave
     uint32_t iblk_base;  //   identity copy
     uint32_t gblk_base;  //   gather: Plan::gsegs segments per wave
-    uint32_t pad;
+    uint32_t fused;      // few enough segments for one workgroup to finish the tensor right after its filter (k_finish)
 };
 static_assert(sizeof(LayerDesc) % 8 == 0, "descriptor table is uploaded as 64-bit words");
 
@@ -126,6 +137,8 @@ struct LayerState {
     uint32_t nchunk;     // chunks of that source (WSEG elements of the tensor, VCHUNK candidates)
     uint32_t t_reserve;  // a lower, safer threshold the filter only counts against (<= t_lo)
     uint32_t refilter;   // t_lo fell short and was replaced by t_reserve: the gather filters every segment again
+    uint32_t done;       // k_finish has written this tensor's output: nothing is left for the later kernels
+    uint32_t pad;
 };
 
 struct Workspace {
@@ -142,6 +155,7 @@ struct Workspace {
     uint32_t *pack_idx;   // [pack_total] the candidates packed per tensor
     uint32_t *pack_val;
     SmallEntry *small;    // [nsmall]
+    uint32_t *redo;       // [L+1] redo[0] = number of tensors k_finish handed back, redo[1..] = their numbers
     size_t bytes;
 };
 
@@ -151,6 +165,7 @@ struct Workspace {
 struct Group {
     uint32_t l0, l1;  // tensors [l0, l1)
     uint32_t filters; // of them through the filter
+    uint32_t unfused; // of those, tensors too large for k_finish: the group needs its own gather
 };
 
 struct Plan {
@@ -161,6 +176,7 @@ struct Plan {
     uint64_t pack_total = 0;
     std::vector<SmallEntry> small; // tensors left to k_small, largest first
     uint64_t nseg_total = 0, cand_total = 0, out_total = 0;
+    bool any_fused = false;
 };
 
 uint32_t sample_piece(uint32_t p, uint32_t stride, uint32_t npieces) {
@@ -169,27 +185,42 @@ uint32_t sample_piece(uint32_t p, uint32_t stride, uint32_t npieces) {
     return q < npieces ? (uint32_t)q : npieces - 1;
 }
 
+// Test hooks: environment switches that choose between execution plans with identical results.
+// They exist for tests and measurements, are read once at the start of a call, and are no part
+// of the interface.
+struct SelectHooks {
+    bool small = true;    // ADACOMP_SELECT_SMALL=0: small tensors take the streaming pipeline too
+    bool fused = true;    // ADACOMP_SELECT_FUSED=0: no tensor is finished by k_finish
+    bool group_tensors = true;  // false with ADACOMP_SELECT_GROUP_MB: only the size limits a group
+    uint64_t group_slots_max = GROUP_BYTES / sizeof(uint2);  // ADACOMP_SELECT_GROUP_MB=<n> (0: one group)
+};
+
+SelectHooks read_select_hooks() {
+    SelectHooks hk;
+    if (const char *e = std::getenv("ADACOMP_SELECT_SMALL")) hk.small = e[0] != '0';
+    if (const char *e = std::getenv("ADACOMP_SELECT_FUSED")) hk.fused = e[0] != '0';
+    if (const char *gm = std::getenv("ADACOMP_SELECT_GROUP_MB")) {
+        const long mb = std::atol(gm);
+        hk.group_slots_max = mb > 0 ? (uint64_t)mb * 1048576ull / sizeof(uint2) : ~0ull;
+        hk.group_tensors = false;
+    }
+    return hk;
+}
+
 int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double rate,
-              const uint64_t *k_override, Plan &plan) {
+              const uint64_t *k_override, const SelectHooks &hk, Plan &plan) {
     if (!(rate >= 0.0 && rate <= 1.0)) return ADACOMP_ERR_RATE;
     plan.desc.clear();
     plan.off.assign((size_t)L + 1, 0);
     uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, iblk = 0;
-    // one workgroup per small tensor, if together they stay cache-sized (ADACOMP_SELECT_SMALL=0:
-    // never, for tests of the pipeline on small tensors)
+    // one workgroup per small tensor, if together they stay cache-sized
     uint64_t small_elems = 0;
     for (uint32_t l = 0; l < L; ++l)
         if (n[l] <= SMALL_MAX) small_elems += n[l];
-    const char *env = std::getenv("ADACOMP_SELECT_SMALL");
-    const bool small_ok = small_elems <= SMALL_TOTAL && !(env && env[0] == '0');
-    // candidate slots per group (ADACOMP_SELECT_GROUP_MB overrides the size for measurements; 0 = one group)
-    uint64_t group_slots_max = GROUP_BYTES / sizeof(uint2);
-    if (const char *gm = std::getenv("ADACOMP_SELECT_GROUP_MB")) {
-        const long mb = std::atol(gm);
-        group_slots_max = mb > 0 ? (uint64_t)mb * 1048576ull / sizeof(uint2) : ~0ull;
-    }
+    const bool small_ok = small_elems <= SMALL_TOTAL && hk.small;
+    const uint64_t group_slots_max = hk.group_slots_max;
     uint64_t pack = 0, cand_max = 0;
-    Group grp{0, 0, 0};
+    Group grp{0, 0, 0, 0};
     for (uint32_t l = 0; l < L; ++l) {
         if (n[l] > 0xffffffffull) return ADACOMP_ERR_LAYER_TOO_LARGE;
         uint64_t k64 = k_override ? k_override[l] : adacomp_count(n[l], rate);
@@ -251,10 +282,11 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
                 uint64_t cap = ((uint64_t)std::ceil(3.0 * per_seg) + 64 + 15) & ~15ull;
                 d.cap = (uint32_t)std::min<uint64_t>(cap, WSEG);
                 const uint64_t slots = (uint64_t)d.nseg * d.cap;
-                if (grp.filters && cand + slots > group_slots_max) {  // close the group, reuse the regions
+                if (grp.filters && (cand + slots > group_slots_max ||
+                                    (hk.group_tensors && grp.filters >= GROUP_TENSORS))) {  // close the group, reuse the regions
                     grp.l1 = (uint32_t)plan.desc.size();
                     plan.groups.push_back(grp);
-                    grp = Group{grp.l1, grp.l1, 0};
+                    grp = Group{grp.l1, grp.l1, 0, 0};
                     cand = 0;
                 }
                 d.cand_base = cand;
@@ -263,6 +295,9 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
                 pack += slots;
                 cand_max = std::max(cand_max, cand);
                 ++grp.filters;
+                d.fused = hk.fused && d.nseg <= FUSE_MAX_SEG && m_est <= (double)FUSE_MAX_CAND;
+                if (d.fused) plan.any_fused = true;
+                else ++grp.unfused;
                 sblk += (d.npieces_s + SPIECES - 1) / SPIECES;
             }
             seg += d.nseg;
@@ -318,6 +353,7 @@ void carve(const Plan &plan, uint32_t L, void *base, Workspace &ws) {
     ws.desc = (LayerDesc *)take(((size_t)L + 1) * sizeof(LayerDesc));
     ws.state = (LayerState *)take((size_t)L * sizeof(LayerState));
     ws.hist = (uint32_t *)take((size_t)L * BINS * sizeof(uint32_t));
+    ws.redo = (uint32_t *)take(((size_t)L + 1) * sizeof(uint32_t));
     ws.seg_cnt = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
     ws.seg_res = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
     ws.seg_gt = (uint32_t *)take(plan.nseg_total * sizeof(uint32_t));
@@ -597,16 +633,20 @@ __global__ __launch_bounds__(BLOCK) void k_pick(Workspace ws) {
         st.k_rem = d.k;
         st.T = 0;
         st.r = 0;
-        st.m = d.n;          // the dense source, unless k_check finds the candidates usable
+        st.m = d.n;          // the dense source, unless the check finds the candidates usable
         st.nchunk = d.nseg;
+        st.done = 0;
+        st.pad = 0;
         ws.state[l] = st;
+        if (l == 0) ws.redo[0] = 0;
     }
 }
 
 // ---- step 3: the streaming read; ordered compaction of key >= t_lo per wave ------
 // Candidates are staged in LDS (one private buffer per wave) and leave as coalesced
-// 8-byte (index, value) stores: one or two store instructions per segment instead of a
-// scattered 4-byte store per candidate.
+// 8-byte (index, value) stores of whole 128-byte lines into the segment's own region of `cap`
+// slots; what does not fit is counted, not stored (a count above `cap` tells the readers to
+// filter that segment again).
 constexpr uint32_t FSTAGE = 272;  // staged candidates per wave: a 256-element piece on top of a 15-entry remainder
 
 __device__ __forceinline__ void wave_lds_fence() {
@@ -713,11 +753,8 @@ __device__ __forceinline__ uint32_t scan_array(Load load, uint32_t *out, uint32_
     return carry;
 }
 
-__global__ __launch_bounds__(CBLOCK) void k_check(Workspace ws, uint32_t l0) {
-    __shared__ uint32_t s_wave[CBLOCK / WAVE];
-    const uint32_t l = l0 + blockIdx.x;
-    const LayerDesc d = ws.desc[l];
-    if (d.mode != MODE_FILTER) return;
+// Whole workgroup.  Returns true if the packed candidates will be the source of the descent.
+__device__ __forceinline__ bool check_tensor(const Workspace &ws, uint32_t l, const LayerDesc &d, uint32_t *s_wave) {
     // the count is exact also where the region overflowed (the gather reads such a segment again)
     const uint32_t *cnt = ws.seg_cnt + d.seg_base, *res = ws.seg_res + d.seg_base;
     uint32_t m = scan_array([&](uint32_t i) { return cnt[i]; }, ws.seg_off + d.seg_base, d.nseg, s_wave);
@@ -728,8 +765,9 @@ __global__ __launch_bounds__(CBLOCK) void k_check(Workspace ws, uint32_t l0) {
         m = scan_array([&](uint32_t i) { return res[i]; }, ws.seg_off + d.seg_base, d.nseg, s_wave);
         refilter = true;
     }
+    const bool usable = !(m < d.k || m > room);
     if (threadIdx.x == 0) {
-        if (m < d.k || m > room) {
+        if (!usable) {
             ws.state[l].use_dense = 1;  // m and nchunk keep the dense-source values
         } else {
             ws.state[l].m = m;
@@ -740,19 +778,17 @@ __global__ __launch_bounds__(CBLOCK) void k_check(Workspace ws, uint32_t l0) {
             }
         }
     }
+    return usable;
 }
 
-// ---- step 5: pack the candidate regions of a tensor, in index order ------------------
+// ---- step 5: pack the candidates of a tensor, in index order --------------------------
+// One wave packs the segments s0 .. s0 + GS - 1 of tensor l.  refilter_all: the regions do not hold
+// the candidates of the threshold in force (it was replaced by the reserve threshold, or the
+// regions have been reused since): every segment is read from the tensor and filtered again.
 template <uint32_t GS>
-__global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L, uint32_t blk0) {
-    const uint32_t blk = blk0 + blockIdx.x;
-    const uint32_t l = find_layer<&LayerDesc::gblk_base>(ws.desc, L, blk);
-    const LayerDesc d = ws.desc[l];
-    if (d.mode != MODE_FILTER || ws.state[l].use_dense) return;
-    const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
-    const uint32_t s0 = ((blk - d.gblk_base) * WAVES + wave) * GS;
-    if (s0 >= d.nseg) return;
-    const bool refilter_all = ws.state[l].refilter != 0;  // the regions hold the candidates of a threshold that fell short
+__device__ __forceinline__ void gather_segments(const Workspace &ws, uint32_t l, const LayerDesc &d, uint32_t s0,
+                                                bool refilter_all) {
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
     uint32_t my_cnt = 0, my_off = 0;
     if (lane < GS && s0 + lane < d.nseg) {
         my_cnt = refilter_all ? 0xffffffffu : ws.seg_cnt[d.seg_base + s0 + lane];
@@ -823,6 +859,38 @@ __global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L, uint
                 }
                 pos += popc64(m[0]) + popc64(m[1]) + popc64(m[2]) + popc64(m[3]);
             });
+        }
+    }
+}
+
+// The tensors of one group that k_finish does not take (too many segments for one workgroup).
+template <uint32_t GS>
+__global__ __launch_bounds__(BLOCK) void k_gather(Workspace ws, uint32_t L, uint32_t blk0) {
+    const uint32_t blk = blk0 + blockIdx.x;
+    const uint32_t l = find_layer<&LayerDesc::gblk_base>(ws.desc, L, blk);
+    const LayerDesc d = ws.desc[l];
+    if (d.mode != MODE_FILTER || d.fused || ws.state[l].use_dense) return;
+    const uint32_t wave = threadIdx.x / WAVE;
+    const uint32_t s0 = ((blk - d.gblk_base) * WAVES + wave) * GS;
+    if (s0 >= d.nseg) return;
+    gather_segments<GS>(ws, l, d, s0, ws.state[l].refilter != 0);
+}
+
+// The tensors that k_finish handed back, after all groups: their regions have been reused by
+// later groups, so every segment is read and filtered again (fixed grid; nothing to do when the
+// list is empty, which is the rule).
+template <uint32_t GS>
+__global__ __launch_bounds__(BLOCK) void k_regather(Workspace ws) {
+    const uint32_t n_redo = ws.redo[0];
+    const uint32_t wave = threadIdx.x / WAVE;
+    for (uint32_t f = 0; f < n_redo; ++f) {
+        const uint32_t l = ws.redo[1 + f];
+        const LayerDesc d = ws.desc[l];
+        if (ws.state[l].use_dense) continue;
+        const uint32_t nblk = (d.nseg + WAVES * GS - 1) / (WAVES * GS);
+        for (uint32_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+            const uint32_t s0 = (blk * WAVES + wave) * GS;
+            if (s0 < d.nseg) gather_segments<GS>(ws, l, d, s0, true);
         }
     }
 }
@@ -1198,6 +1266,270 @@ __global__ __launch_bounds__(SBLOCK) void k_small(const SmallEntry *S, const uin
     }
 }
 
+// ---- steps 4-7 for one tensor in one workgroup ---------------------------------------
+// A tensor of up to a couple of thousand segments has tens of thousands of candidates: half a
+// megabyte that the filter of its group has just written and that is still in cache.  One
+// workgroup per tensor, launched right after that filter, takes it from there to its output with
+// no further launches:
+//   pack     every wave copies the regions of a contiguous range of segments to the packed arrays,
+//            in index order (a segment whose region overflowed is read from the tensor and filtered
+//            again), and bins (key - t_lo) >> 11 into 4096 bins (keys a factor two or more above
+//            t_lo share the last bin) -> the bin of the k-th largest key;
+//   level 2  histogram of the low 11 bits inside that bin over the packed candidates -> the exact
+//            threshold key T and the tie quota r;
+//   count    every wave counts key > T and key == T in its even share of the packed candidates;
+//   emit     ordered write: a wave's first output position follows from the counts of the waves
+//            before it; the selected pairs pass through an LDS buffer and leave in whole runs.
+// The last three are dense reads of data the workgroup has just written.  The workgroup does
+// the check of the multi-launch path instead and leaves the tensor to those kernels when the
+// candidates are too few (the sample misjudged: filtered again after all groups) or too many,
+// and after packing when the threshold lies a factor two above t_lo (the packed arrays are then
+// ready for the descent).  A tensor that the plan does not give to this kernel (more than
+// FUSE_MAX_SEG segments or FUSE_MAX_CAND expected candidates) only gets the check here.
+constexpr uint32_t ESTAGE = 384;  // selected pairs a wave of k_finish collects before it writes them out
+
+__global__ __launch_bounds__(SBLOCK) void k_finish(Workspace ws, uint32_t l0, uint32_t *out_idx, uint32_t *out_val) {
+    static_assert(SBLOCK == CBLOCK, "the check and the finish share a workgroup");
+    static_assert(ESTAGE > PIECE && ESTAGE * 2 * SWAVES >= BINS, "emit buffer: more than a piece; it shares LDS with the histogram");
+    __shared__ uint32_t s_buf[2 * ESTAGE * SWAVES];  // first the histogram, then the waves' emit buffers (index, value)
+    __shared__ uint16_t s_cnt[FUSE_MAX_SEG];
+    __shared__ uint32_t s_wave[SWAVES];
+    __shared__ uint32_t s_first[SWAVES], s_gt[SWAVES], s_eq[SWAVES];
+    __shared__ uint32_t s_res[2];
+    uint32_t *s_hist = s_buf;
+    const uint32_t l = l0 + blockIdx.x;
+    const LayerDesc d = ws.desc[l];
+    if (d.mode != MODE_FILTER) return;
+    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wv = tid / WAVE;
+    const uint32_t per = (d.nseg + SWAVES - 1) / SWAVES;  // segments per wave
+    const uint32_t s_lo = wv * per < d.nseg ? wv * per : d.nseg;
+    const uint32_t s_hi = s_lo + per < d.nseg ? s_lo + per : d.nseg;
+    bool take = d.fused != 0;
+    uint32_t m = 0;
+    if (take) {
+        // counts of all segments into LDS; candidates per wave and in all
+        const uint32_t *cnt = ws.seg_cnt + d.seg_base;
+        for (uint32_t i = tid; i < d.nseg; i += SBLOCK) s_cnt[i] = (uint16_t)cnt[i];  // at most WSEG
+        for (uint32_t i = tid; i < BINS; i += SBLOCK) s_hist[i] = 0;
+        __syncthreads();
+        uint32_t mine = 0;  // this wave's candidates (wave-uniform after the reduction)
+        for (uint32_t i = s_lo + lane; i < s_hi; i += WAVE) mine += s_cnt[i];
+#pragma unroll
+        for (int o = WAVE / 2; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+        if (lane == 0) s_first[wv] = mine;
+        __syncthreads();
+        uint32_t first = 0;
+        for (uint32_t w = 0; w < SWAVES; ++w) {
+            if (w < wv) first += s_first[w];
+            m += s_first[w];
+        }
+        __syncthreads();
+        if (lane == 0) s_first[wv] = first;  // packed position of the wave's first candidate
+        const uint64_t room = std::min<uint64_t>((uint64_t)d.nseg * d.cap, d.n / 4);
+        take = m >= d.k && m <= 2 * FUSE_MAX_CAND && m <= room;
+    }
+    if (!take) {
+        // the multi-launch path; a tensor that was meant to be finished here has no gather in its
+        // group: it is entered into the list of tensors to be filtered again after all groups
+        const bool usable = check_tensor(ws, l, d, s_wave);
+        if (tid == 0 && d.fused && usable) {
+            ws.state[l].refilter = 1;
+            ws.redo[1 + atomicAdd(&ws.redo[0], 1u)] = l;
+        }
+        return;
+    }
+    const uint32_t t_lo = ws.state[l].t_lo;
+    uint32_t *__restrict__ pidx = ws.pack_idx + d.pack_base;
+    uint32_t *__restrict__ pval = ws.pack_val + d.pack_base;
+    {   // pack + first histogram
+        const uint2 *__restrict__ regions = ws.cand + d.cand_base;
+        const Source dense{reinterpret_cast<const uint32_t *>(d.g), nullptr, d.n, WSEG, d.vec != 0};
+        auto bin_of = [&](uint32_t bits) {
+            const uint32_t b = (mag_key(bits) - t_lo) >> FUSE_SHIFT;
+            return b < BINS - 1 ? b : BINS - 1;
+        };
+        uint32_t pos = s_first[wv];  // wave-uniform
+        for (uint32_t s0 = s_lo; s0 < s_hi; s0 += FUSE_SB) {
+            uint32_t cnt[FUSE_SB];
+            uint2 a[FUSE_SB];
+            uint32_t over = 0;  // segments of the batch whose region overflowed (bit j)
+#pragma unroll
+            for (uint32_t j = 0; j < FUSE_SB; ++j) {
+                cnt[j] = s0 + j < s_hi ? __builtin_amdgcn_readfirstlane((uint32_t)s_cnt[s0 + j]) : 0u;
+                if (cnt[j] > d.cap) over |= 1u << j;
+                else if (lane < cnt[j]) a[j] = regions[(uint64_t)(s0 + j) * d.cap + lane];
+            }
+            const uint32_t pos0 = pos;
+#pragma unroll
+            for (uint32_t j = 0; j < FUSE_SB; ++j) {
+                if (cnt[j] <= d.cap) {  // uniform
+                    if (lane < cnt[j]) {
+                        pidx[pos + lane] = a[j].x;
+                        pval[pos + lane] = a[j].y;
+                        atomicAdd(&s_hist[bin_of(a[j].y)], 1u);
+                    }
+                    for (uint32_t e = WAVE + lane; e < cnt[j]; e += WAVE) {
+                        const uint2 c = regions[(uint64_t)(s0 + j) * d.cap + e];
+                        pidx[pos + e] = c.x;
+                        pval[pos + e] = c.y;
+                        atomicAdd(&s_hist[bin_of(c.y)], 1u);
+                    }
+                }
+                pos += cnt[j];
+            }
+            if (over) {  // those regions hold only the first `cap` candidates: filter the segments again
+                uint32_t p0 = pos0;
+#pragma unroll 1
+                for (uint32_t j = 0; j < FUSE_SB && s0 + j < s_hi; ++j) {
+                    const uint32_t c_j = __builtin_amdgcn_readfirstlane((uint32_t)s_cnt[s0 + j]);
+                    if ((over >> j) & 1u) {
+                        const uint32_t lo = (s0 + j) * WSEG;
+                        const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
+                        uint32_t q0 = p0;
+                        visit_range<false, false, 4>(dense, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+                            bool f[4];
+                            uint64_t mk[4];
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                f[c] = (uint32_t)c < nvalid && mag_key(bits[c]) >= t_lo;
+                                mk[c] = __ballot(f[c]);
+                            }
+                            uint32_t p = q0 + lanes_below(mk[0]) + lanes_below(mk[1]) + lanes_below(mk[2]) + lanes_below(mk[3]);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                if (f[c]) {
+                                    pidx[p] = idx[c];
+                                    pval[p] = bits[c];
+                                    atomicAdd(&s_hist[bin_of(bits[c])], 1u);
+                                    ++p;
+                                }
+                            }
+                            q0 += popc64(mk[0]) + popc64(mk[1]) + popc64(mk[2]) + popc64(mk[3]);
+                        });
+                    }
+                    p0 += c_j;
+                }
+            }
+        }
+    }
+    __syncthreads();  // the packed arrays are complete and visible to the whole workgroup
+    small_find_bin(s_hist, BINS, d.k, s_wave, s_res);
+    const uint32_t b0 = s_res[0];
+    const uint32_t k_rem = d.k - s_res[1];
+    __syncthreads();
+    if (b0 == BINS - 1) {  // keys of different upper bits share the last bin: the general descent resolves it
+        if (tid == 0) {
+            ws.state[l].m = m;
+            ws.state[l].nchunk = (m + VCHUNK - 1) / VCHUNK;
+        }
+        return;
+    }
+    // the wave's even share of the packed candidates, in whole pieces
+    const Source packed{pval, pidx, m, VCHUNK, true};
+    const uint32_t share = ((m + SWAVES - 1) / SWAVES + PIECE - 1) / PIECE * PIECE;
+    const uint32_t c_lo = wv * share < m ? wv * share : m;
+    const uint32_t c_hi = m - c_lo < share ? m : c_lo + share;
+    for (uint32_t i = tid; i < (1u << FUSE_SHIFT); i += SBLOCK) s_hist[i] = 0;
+    __syncthreads();
+    visit_range<false, false, 4>(packed, c_lo, c_hi, [&](const uint32_t(&)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t rel = mag_key(bits[c]) - t_lo;
+            if ((uint32_t)c < nvalid && (rel >> FUSE_SHIFT) == b0) atomicAdd(&s_hist[rel & ((1u << FUSE_SHIFT) - 1u)], 1u);
+        }
+    });
+    __syncthreads();
+    small_find_bin(s_hist, 1u << FUSE_SHIFT, k_rem, s_wave, s_res);
+    const uint32_t T = t_lo + (b0 << FUSE_SHIFT) + s_res[0];  // threshold key
+    const uint32_t r = k_rem - s_res[1];                      // entries equal to it to keep (lowest indices)
+    uint32_t n_gt = 0, n_eq = 0;
+    visit_range<false, false, 4>(packed, c_lo, c_hi, [&](const uint32_t(&)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t key = mag_key(bits[c]);
+            const bool ok = (uint32_t)c < nvalid;
+            n_gt += popc64(__ballot(ok && key > T));
+            n_eq += popc64(__ballot(ok && key == T));
+        }
+    });
+    if (lane == 0) {
+        s_gt[wv] = n_gt;
+        s_eq[wv] = n_eq;
+    }
+    __syncthreads();  // also: the histogram is no longer needed, its memory becomes the emit buffers
+    uint32_t run_gt = 0, run_eq = 0;  // entries with key > T / key == T before the current ones (in the tensor)
+    for (uint32_t w = 0; w < wv; ++w) {
+        run_gt += s_gt[w];
+        run_eq += s_eq[w];
+    }
+    // Selected pairs go to this wave's LDS buffer in order and leave as runs of consecutive
+    // output entries: a few full-width stores instead of eight narrow strided ones per piece.
+    const uint32_t first_out = run_gt + (run_eq < r ? run_eq : r);  // output position of the wave's first selected entry
+    uint32_t *e_idx = s_buf + wv * 2 * ESTAGE, *e_val = e_idx + ESTAGE;
+    uint32_t *oi = out_idx + d.out_off + first_out;
+    uint32_t *ov = out_val + d.out_off + first_out;
+    uint32_t staged = 0, written = 0;  // wave-uniform
+    auto drain = [&]() {
+        wave_lds_fence();
+        for (uint32_t e = lane; e < staged; e += WAVE) {
+            oi[written + e] = e_idx[e];
+            ov[written + e] = e_val[e];
+        }
+        wave_lds_fence();
+        written += staged;
+        staged = 0;
+    };
+    visit_range<true, false, 4>(packed, c_lo, c_hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+        bool g[4], e[4];
+        uint64_t any = 0;
+        uint32_t gt_b = run_gt, eq_b = run_eq, tot_g = 0, tot_e = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t key = mag_key(bits[c]);
+            const bool ok = (uint32_t)c < nvalid;
+            g[c] = ok && key > T;
+            e[c] = ok && key == T;
+            const uint64_t mg = __ballot(g[c]), me = __ballot(e[c]);
+            any |= mg | me;
+            gt_b += lanes_below(mg);
+            eq_b += lanes_below(me);
+            tot_g += popc64(mg);
+            tot_e += popc64(me);
+        }
+        if (any == 0) return;
+        if (staged + PIECE > ESTAGE) drain();  // uniform: a piece adds at most PIECE entries
+        const uint32_t origin = first_out + written;  // output position of buffer slot 0
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            // an entry at the threshold is kept iff fewer than r equal keys precede it in the tensor
+            if (g[c]) {
+                const uint32_t slot = gt_b + (eq_b < r ? eq_b : r) - origin;
+                e_idx[slot] = idx[c];
+                e_val[slot] = bits[c];
+                ++gt_b;
+            } else if (e[c]) {
+                if (eq_b < r) {
+                    const uint32_t slot = gt_b + eq_b - origin;
+                    e_idx[slot] = idx[c];
+                    e_val[slot] = bits[c];
+                }
+                ++eq_b;
+            }
+        }
+        run_gt += tot_g;
+        run_eq += tot_e;
+        staged = run_gt + (run_eq < r ? run_eq : r) - origin;
+    });
+    drain();
+    if (tid == 0) {
+        ws.state[l].T = T;
+        ws.state[l].r = r;
+        ws.state[l].done = 1;
+        ws.state[l].m = 0;
+        ws.state[l].nchunk = 0;  // nothing for the descent, count and emit kernels
+    }
+}
+
 // ---- chunk numbering across tensors ------------------------------------------------
 // The descent, count and emit kernels run with a fixed number of workgroups; each worker
 // (workgroup or wave) takes a contiguous range of the global chunk numbering.
@@ -1281,6 +1613,7 @@ __global__ __launch_bounds__(BLOCK) void k_resolve(Workspace ws) {
     if (d.nseg == 0) return;
     uint32_t *h = ws.hist + (size_t)l * BINS;
     const LayerState st = ws.state[l];
+    if (st.done) return;
     constexpr uint32_t nbins = LEVEL == 2 ? 128u : BINS;
     uint32_t bin, above;
     find_bin_from_top(h, nbins, st.k_rem, bin, above);
@@ -1483,7 +1816,7 @@ extern "C" int adacomp_select_workspace(const uint64_t *n, uint32_t L, double ra
                                         const uint64_t *k_override, size_t *bytes) {
     if (!bytes || (L && !n)) return ADACOMP_ERR_NULL;
     Plan plan;
-    int rc = make_plan(n, nullptr, L, rate, k_override, plan);
+    int rc = make_plan(n, nullptr, L, rate, k_override, read_select_hooks(), plan);
     if (rc) return rc;
     Workspace ws;
     carve(plan, (uint32_t)plan.desc.size() - 1, nullptr, ws);
@@ -1557,7 +1890,7 @@ int select_impl(const adacomp_layer_t *layers, uint32_t L, double rate, const ui
         if ((uintptr_t)data[l] & 3u) return ADACOMP_ERR_ALIGNMENT;
     }
     Plan plan;
-    int rc = make_plan(n.data(), data.data(), L, rate, k_override, plan);
+    int rc = make_plan(n.data(), data.data(), L, rate, k_override, read_select_hooks(), plan);
     if (rc) return rc;
     if (plan.out_total > out->cap) return ADACOMP_ERR_CAPACITY;
     if (plan.out_total && (!out->idx || !out->val)) return ADACOMP_ERR_NULL;
@@ -1604,12 +1937,20 @@ int select_impl(const adacomp_layer_t *layers, uint32_t L, double rate, const ui
             if (!g.filters) continue;
             const uint32_t w0 = plan.desc[g.l0].wblk_base, g0 = plan.desc[g.l0].gblk_base;
             LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, plan.desc[g.l1].wblk_base - w0, ws, Lp, w0);
-            ADACOMP_LAUNCH(ADACOMP_KERNEL_CHECK, k_check, dim3(g.l1 - g.l0), dim3(CBLOCK), s, ws, g.l0);
+            // per tensor: finished on the spot, or checked and left to the kernels below
+            ADACOMP_LAUNCH(ADACOMP_KERNEL_FINISH, k_finish, dim3(g.l1 - g.l0), dim3(SBLOCK), s, ws, g.l0, out_idx, out_val);
             if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
+            if (!g.unfused) continue;  // no tensor of this group needs its regions packed before they are reused
             const uint32_t g_blocks = plan.desc[g.l1].gblk_base - g0;
             if (plan.gsegs == GSEGS) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS>, g_blocks, ws, Lp, g0);
             else if (plan.gsegs == GSEGS_MID) LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_MID>, g_blocks, ws, Lp, g0);
             else LAUNCH(ADACOMP_KERNEL_GATHER, k_gather<GSEGS_FULL>, g_blocks, ws, Lp, g0);
+        }
+        if (plan.any_fused) {  // the tensors that k_finish handed back (usually none)
+            const uint32_t r_blocks = (uint32_t)std::min<uint64_t>(2 * TAIL_BLOCKS, (tot.seg_base + WAVES - 1) / WAVES);
+            if (plan.gsegs == GSEGS) LAUNCH(ADACOMP_KERNEL_GATHER, k_regather<GSEGS>, r_blocks, ws);
+            else if (plan.gsegs == GSEGS_MID) LAUNCH(ADACOMP_KERNEL_GATHER, k_regather<GSEGS_MID>, r_blocks, ws);
+            else LAUNCH(ADACOMP_KERNEL_GATHER, k_regather<GSEGS_FULL>, r_blocks, ws);
         }
     }
     if (tot.seg_base) {

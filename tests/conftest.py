@@ -10,6 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "fused_only: GPU select test that is not repeated with the finish kernel switched off")
 
 
 def pytest_collection_modifyitems(config, items):

@@ -555,6 +555,36 @@ def test_global_staleness_rule_of_the_competitors(ac, dev):
     assert any(not np.array_equal(a, b) for a, b in zip(want, per_param)), "the two rules must differ here"
 
 
+def test_global_and_per_parameter_calls_mixed_on_one_state(ac, dev):
+    """Calls under the competitors' rule enter their updates into the trace like any other, so a later
+    per-parameter call that looks back across them counts them (eq. 3 asks which updates touched
+    the parameter, not which rule set their step)."""
+    rng = np.random.default_rng(53)
+    sizes, Q, d = [4000, 9, 300], 36, 12
+    ups = random_updates(rng, sizes, Q, 0.15, zero_frac=0.1)
+    pulls = [int(rng.integers(max(0, q - d), q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    calls = [(0, 5, "per"), (5, 9, "global"), (9, 10, "per"), (10, 20, "global"), (20, 27, "per"), (27, 36, "per")]
+    theta = [torch.from_numpy(t.copy()).to(dev) for t in theta0]
+    us = [ac.Update.from_host(o, i, v, dev, pull_ts=p) for (o, i, v), p in zip(ups, pulls)]
+    st = ac.State(theta, history=d)
+    want = [t.copy() for t in theta0]
+    ps = oracle.ParameterServer(want)
+    for a, b, rule in calls:
+        part = us[a:b]
+        if rule == "per":
+            ws = torch.empty(max(ac.adacomp_apply_workspace(sizes, part, st), 256), dtype=torch.uint8, device=dev)
+            ac.adacomp_apply(theta, st, part, 0.04, ws)
+        else:
+            ws = torch.empty(1 << 12, dtype=torch.uint8, device=dev)
+            ac.adacomp_apply_global_staleness(theta, st, part, 0.04, ws)
+        for q in range(a, b):
+            ps.apply(*ups[q], pulls[q], 0.04, mode=oracle.PER_PARAMETER if rule == "per" else oracle.GLOBAL)
+    torch.cuda.synchronize()
+    assert st.t == Q
+    assert compare([t.cpu().numpy() for t in theta], want, "global and per-parameter calls mixed") == 0
+
+
 def test_update_validate_and_malformed_entries_are_skipped(ac, dev, monkeypatch):
     rng = np.random.default_rng(52)
     sizes = [3000, 40]

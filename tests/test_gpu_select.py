@@ -22,6 +22,18 @@ def dev():
     return torch.device("cuda:0")
 
 
+@pytest.fixture(autouse=True, params=["finish kernel", "multi-launch"])
+def finish_mode(request, monkeypatch):
+    """Every test of this file runs twice: with tensors finished by one workgroup each right after
+    their filter (the default), and with that kernel switched off (check, gather, descent, count,
+    scan and emit launches for every tensor).  Tests marked fused_only skip the second run."""
+    if request.param == "multi-launch":
+        if request.node.get_closest_marker("fused_only"):
+            pytest.skip("run with the finish kernel only")
+        monkeypatch.setenv("ADACOMP_SELECT_FUSED", "0")
+    return request.param
+
+
 def host(tensors):
     return [t.cpu().numpy() for t in tensors]
 
@@ -172,6 +184,7 @@ def test_negation_and_scaling_invariance_on_gpu(ac, dev):
     assert np.array_equal(a[1], c[1]) and np.array_equal(a[2] * np.float32(4.0), c[2])
 
 
+@pytest.mark.fused_only
 def test_flat_config_full_size(ac, dev):
     """The roofline configuration in the launch shape bench.py times: 100 tensors of 10M entries,
     rate 0.5%, one call.  The oracle checks sampled tensors entry by entry; on all 100 the
@@ -417,3 +430,42 @@ def test_row_scaled_gradients_in_many_groups(ac, dev, monkeypatch, group_mb):
         tensors.append(x * scale.repeat_interleave(row)[:n])
     for rate in (0.002, 0.02, 0.1):
         check(ac, tensors, rate, what=f"row-scaled, groups of {group_mb} MB, rate {rate}")
+
+
+def test_finish_kernel_hands_back_what_it_cannot_resolve(ac, dev):
+    """One workgroup finishes a tensor only if the threshold lies less than a factor two above the
+    filter threshold and few regions overflowed; otherwise the tensor goes back to the launches
+    that work for anything.  Forced here: (a) values whose k-th largest lies far above the
+    threshold the sample suggests (every sampled piece is small, the large values sit elsewhere);
+    (b) ties: thousands of equal magnitudes at the threshold, more than a wave can keep in LDS,
+    so that its counts come from one more pass; (c) many overflowing regions next to tensors that
+    are finished normally, in one call, several groups."""
+    gen = torch.Generator(device=dev).manual_seed(2718)
+    n = 3_000_001
+    a = torch.randn(n, generator=gen, device=dev) * 1e-3
+    a[5::97] = torch.randn(a[5::97].numel(), generator=gen, device=dev) * 50.0      # 1% of the entries, 4 orders larger
+    b = torch.randn(n, generator=gen, device=dev) * 1e-3
+    top = torch.topk(b.abs(), 40_000).values[-1]
+    b[1_000_000:1_030_000] = torch.where(torch.rand(30_000, generator=gen, device=dev) < 0.5, -top, top)   # 30,000 ties in one stretch
+    c = torch.randn(n, generator=gen, device=dev) * 1e-3
+    for s0 in range(0, n - 8192, 5 * 8192):
+        c[s0:s0 + 6000] = torch.randn(6000, generator=gen, device=dev)
+    d = torch.randn(1_500_000, generator=gen, device=dev)
+    for rate in (0.002, 0.012, 0.05):
+        check(ac, [a, b, c, d], rate, what="finish kernel, special cases")
+    check(ac, [b, d], 0.5, k_override=[40_000 + 7, 3], what="finish kernel, tie quota")
+
+
+def test_finish_kernel_sizes_around_its_limits(ac, dev):
+    """Tensors of 4095, 4096 and 4097 segments (the last is not finished by one workgroup and takes
+    the gather of its group), a single segment, a ragged last segment of one element."""
+    gen = torch.Generator(device=dev).manual_seed(31415)
+    sizes = [8192 * 4095 + 1, 8192 * 4096, 8192 * 4096 + 1, 300_000, 8192 * 40 + 1]
+    g = [torch.randn(n, generator=gen, device=dev) * (10.0 ** -(i % 3)) for i, n in enumerate(sizes)]
+    u = gpu_select(ac, g, 0.003)
+    want = oracle_select_parallel([[t.cpu().numpy()] for t in g], 0.003, threads=5)
+    for l, (o, i, v) in enumerate(want):
+        a, k = u.offsets[l], int(o[1])
+        assert u.offsets[l + 1] - a == k
+        assert np.array_equal(u.idx[a:a + k].cpu().numpy().view(np.uint32), i), f"tensor {l}"
+        assert np.array_equal(u.val[a:a + k].cpu().numpy().view(np.uint32), v.view(np.uint32)), f"tensor {l}"
