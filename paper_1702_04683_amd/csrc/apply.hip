@@ -46,7 +46,9 @@ namespace {
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t WAVES = BLOCK / WAVE;
 constexpr uint32_t ITEMS = 4;          // scatter plan: entries per thread
-constexpr uint32_t TILE_MAX = 2048;    // sweep plan: most coordinates per tile (power of two); dense queues get smaller tiles
+constexpr uint32_t TILE_MAX = 2048;    // sweep plan: most coordinates per tile of the sorting kernels (power of two); dense queues get smaller tiles
+constexpr uint32_t TILE_MAX_SPARSE = 4096;  // ... and of the kernel for sparse queues
+constexpr uint32_t HOT_TILE_MAX = TILE_MAX_SPARSE;  // largest tile the kernel for overflowing tiles keeps in LDS
 constexpr uint32_t STAGE_CAP = 512;    // sweep plan: entries of the whole queue a tile can hold in LDS
 constexpr uint32_t SLOW_GRID = 1024;
 constexpr uint32_t PASS = 256;           // sweep plan: updates whose slices are staged together
@@ -55,6 +57,8 @@ constexpr uint32_t DENSE_QMAX = 256;     // sweep plan: longest queue the kernel
 // ... and the queued entries per parameter from which it is used, for queues of up to 64 updates
 // and for longer ones (measured crossovers against the sorting kernels: 0.5-1.0 and 1.4-1.8)
 constexpr double DENSE_PER_COORD = 1.0, DENSE_PER_COORD_LONG = 1.75;
+// ... and the queued entries per parameter up to which the kernel for sparse queues is used
+constexpr double SPARSE_PER_COORD = 0.25;
 // one launch costs about as much as this many bytes of memory traffic (4 us at 5 TB/s)
 constexpr double LAUNCH_COST_BYTES = 20e6;
 static_assert((TILE_MAX & (TILE_MAX - 1)) == 0 && TILE_MAX >= BLOCK && STAGE_CAP % BLOCK == 0 && STAGE_CAP <= 65535,
@@ -715,6 +719,254 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_short(Sweep sw) {
     }
 }
 
+// The sweep for sparse queues of at most PASS_SHORT updates: most parameters that the queue
+// touches at all are touched once (16 workers at 0.5 %: 93 % of them), and such a touch needs no
+// list, no rank and no sorting: sigma_k counts earlier touches of k (eq. 3) and there are none,
+// so the step is Theta_k - alpha * v straight from the registers that hold the entry.  Which
+// touches are alone is read off two bitmaps over the tile's coordinates (touched at all / touched
+// at least twice), filled with LDS atomics.  Only the entries of coordinates touched twice or more
+// are grouped: the coordinate's number among those coordinates is a population count over the
+// second bitmap, so the counting sort runs over a few dozen slots instead of the tile's thousands.
+// A workgroup takes TPB consecutive tiles of up to TILE_MAX_SPARSE coordinates: wave 0 fetches
+// the bounds of every update in all of them, then every thread requests its entries of all TPB
+// tiles together, then the parameters they name (the chain bounds -> entries -> parameters is paid
+// once per workgroup), and only then the tiles are worked through one after the other.  A tile
+// with more than SP_CAP queued entries or SP_MULTI entries on shared coordinates is left untouched
+// for the kernel for overflowing tiles.
+constexpr uint32_t SP_PER = 3;                 // entries per thread and tile
+constexpr uint32_t SP_CAP = BLOCK * SP_PER;    // entries per tile
+constexpr uint32_t SP_MULTI = 512;             // entries on coordinates touched more than once
+constexpr uint32_t SP_WORDS = TILE_MAX_SPARSE / 32;
+static_assert(SP_WORDS <= BLOCK && SP_MULTI % BLOCK == 0 && SP_MULTI / 2 <= BLOCK,
+              "one bitmap word, two list slots, one shared coordinate per thread");
+
+template <uint32_t TPB>
+__global__ __launch_bounds__(BLOCK) void k_sweep_sparse(Sweep sw) {
+    constexpr uint32_t QS = PASS_SHORT;
+    __shared__ uint32_t s_b1[SP_WORDS], s_b2[SP_WORDS];  // coordinate touched / touched at least twice
+    __shared__ uint32_t s_pref[SP_WORDS];                // coordinates with the second bit set before this word
+    __shared__ uint32_t s_start[SP_MULTI / 2 + 1];       // per shared coordinate: count, then start of its list
+    __shared__ uint32_t s_fill[SP_MULTI / 2];
+    __shared__ uint32_t s_key[SP_MULTI];
+    __shared__ float s_val[SP_MULTI], s_theta[SP_MULTI], s_prod[SP_MULTI];
+    __shared__ uint16_t s_coord[SP_MULTI], s_slot[SP_MULTI];
+    __shared__ const uint32_t *s_idx[QS];
+    __shared__ const float *s_valp[QS];
+    __shared__ const uint32_t *s_pre[QS];
+    __shared__ uint32_t s_tag[QS];
+    __shared__ uint32_t s_off[TPB][QS + 1];  // per tile: staged position of the first entry of update q; [Q..QS] = entries
+    __shared__ uint32_t s_b0[TPB][QS];
+    __shared__ uint32_t s_wave[WAVES];
+    __shared__ uint32_t s_bad[TPB];
+    static_assert(QS == WAVE, "wave 0 serves one update per lane");
+
+    const uint32_t tid = threadIdx.x, t0 = blockIdx.x * TPB;
+    const uint32_t tile = 1u << sw.tile_shift;
+    uint32_t tensor[TPB];
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) tensor[i] = t0 + i < sw.ntiles ? sw.tile_tensor[t0 + i] : 0u;
+    if (tid < WAVE) {  // wave 0: the slices of every update in the TPB tiles, their scans, the updates' arrays
+        const bool mine = tid < sw.Q;
+        uint32_t row[TPB + 1];
+        if (mine) {
+            const uint32_t *b = sw.B + (uint64_t)tid * (sw.ntiles + 1) + t0;
+#pragma unroll
+            for (uint32_t i = 0; i <= TPB; ++i) row[i] = t0 + i <= sw.ntiles ? b[i] : 0u;
+            const UpdDesc u = sw.U[tid];
+            s_idx[tid] = u.idx;
+            s_valp[tid] = u.val;
+            s_pre[tid] = u.pre;
+            s_tag[tid] = tid | ((tid - u.pull) << 15);
+        }
+#pragma unroll
+        for (uint32_t i = 0; i < TPB; ++i) {
+            // bounds of an unsorted (malformed) list may cross
+            const uint32_t len = (mine && t0 + i < sw.ntiles && row[i + 1] >= row[i]) ? row[i + 1] - row[i] : 0u;
+            uint32_t incl = len;
+#pragma unroll
+            for (int d = 1; d < WAVE; d <<= 1) {
+                const uint32_t y = __shfl_up(incl, d);
+                if (tid >= (uint32_t)d) incl += y;
+            }
+            s_off[i][tid] = incl - len;  // lanes at or beyond Q hold the total
+            if (tid == WAVE - 1) s_off[i][QS] = incl;
+            if (mine) s_b0[i][tid] = row[i];
+        }
+    }
+    if (tid < TPB) s_bad[tid] = 0;
+    __syncthreads();
+
+    float *theta_of[TPB];  // first parameter of the tile
+    uint32_t c0[TPB], ncoord[TPB], total[TPB];
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+        const ParamDesc pd = sw.P[tensor[i]];
+        c0[i] = (t0 + i - (uint32_t)pd.tile_base) << sw.tile_shift;
+        ncoord[i] = pd.n - c0[i] < tile ? (uint32_t)(pd.n - c0[i]) : tile;
+        theta_of[i] = pd.theta + c0[i];
+        total[i] = t0 + i < sw.ntiles ? s_off[i][QS] : 0u;
+    }
+    // every entry of every tile of the workgroup, then the parameters they name: two rounds of requests
+    uint32_t c[TPB][SP_PER], key[TPB][SP_PER];
+    float v[TPB][SP_PER], th[TPB][SP_PER];
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+#pragma unroll
+        for (uint32_t j = 0; j < SP_PER; ++j) {
+            const uint32_t p = tid + j * BLOCK;
+            c[i][j] = 0xffffffffu;
+            v[i][j] = 0.f;
+            key[i][j] = 0;
+            if (total[i] <= SP_CAP && p < total[i]) {
+                const uint32_t u = slice_of(s_off[i], sw.Q, p);
+                const uint32_t e = s_b0[i][u] + (p - s_off[i][u]);
+                c[i][j] = s_idx[u][e] - c0[i];
+                v[i][j] = s_valp[u][e];
+                key[i][j] = s_tag[u];
+                if (s_pre[u]) {
+                    const uint32_t before = s_pre[u][e];
+                    if (before > 0x7fffu) s_bad[i] = 1;  // does not fit the key
+                    key[i][j] = (key[i][j] & 0x7fffu) | (before << 15) | 0x40000000u;
+                }
+                if (c[i][j] >= ncoord[i]) s_bad[i] = 1;  // only a malformed (unsorted) index list gets here
+            }
+        }
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+#pragma unroll
+        for (uint32_t j = 0; j < SP_PER; ++j) {
+            th[i][j] = 0.f;
+            if (c[i][j] < ncoord[i]) th[i][j] = theta_of[i][c[i][j]];
+        }
+    }
+
+#pragma unroll
+    for (uint32_t i = 0; i < TPB; ++i) {
+        if (total[i] == 0) continue;  // uniform
+        if (total[i] > SP_CAP) {      // uniform: leave the tile untouched for the kernel for overflowing tiles
+            if (tid == 0) sw.ovf[1 + atomicAdd(&sw.ovf[0], 1u)] = t0 + i;
+            continue;
+        }
+        __syncthreads();  // the previous tile is done with the LDS arrays
+        if (tid < SP_WORDS) {
+            s_b1[tid] = 0;
+            s_b2[tid] = 0;
+        }
+        for (uint32_t x = tid; x < SP_MULTI / 2; x += BLOCK) {
+            s_start[x] = 0;
+            s_fill[x] = 0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t j = 0; j < SP_PER; ++j) {
+            if (c[i][j] < ncoord[i]) {
+                const uint32_t bit = 1u << (c[i][j] & 31u);
+                if (atomicOr(&s_b1[c[i][j] >> 5], bit) & bit) atomicOr(&s_b2[c[i][j] >> 5], bit);
+            }
+        }
+        __syncthreads();
+        // shared coordinates numbered in coordinate order: prefix population count of the second bitmap
+        uint32_t shared_all;
+        {
+            const uint32_t mine = tid < SP_WORDS ? (uint32_t)__popc(s_b2[tid]) : 0u;
+            const uint32_t before = block_exclusive_scan<WAVES>(mine, s_wave, shared_all);
+            if (tid < SP_WORDS) s_pref[tid] = before;
+        }
+        __syncthreads();
+        if (s_bad[i] || shared_all > SP_MULTI / 2) {  // uniform
+            if (tid == 0) sw.ovf[1 + atomicAdd(&sw.ovf[0], 1u)] = t0 + i;
+            continue;
+        }
+        // the entries on shared coordinates are counted per coordinate; nothing is stored before the
+        // tile is known to fit, so that a tile left to the other kernel is found untouched
+        uint32_t slot[SP_PER];
+#pragma unroll
+        for (uint32_t j = 0; j < SP_PER; ++j) {
+            slot[j] = 0xffffffffu;
+            if (c[i][j] >= ncoord[i]) continue;
+            const uint32_t w = c[i][j] >> 5, bit = 1u << (c[i][j] & 31u);
+            const uint32_t twice = s_b2[w];
+            if (twice & bit) {
+                slot[j] = s_pref[w] + (uint32_t)__popc(twice & (bit - 1u));
+                atomicAdd(&s_start[slot[j]], 1u);
+            }
+        }
+        uint32_t multi = 0;  // entries on shared coordinates
+        if (shared_all) {    // uniform
+            __syncthreads();
+            const uint32_t n_touch = tid < shared_all ? s_start[tid] : 0u;
+            const uint32_t before = block_exclusive_scan<WAVES>(n_touch, s_wave, multi);  // counts -> list starts
+            if (tid < shared_all) s_start[tid] = before;
+            if (tid == 0) s_start[shared_all] = multi;
+            __syncthreads();
+            if (multi > SP_MULTI) {  // uniform
+                if (tid == 0) sw.ovf[1 + atomicAdd(&sw.ovf[0], 1u)] = t0 + i;
+                continue;
+            }
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < SP_PER; ++j) {
+            if (c[i][j] >= ncoord[i]) continue;
+            if (slot[j] == 0xffffffffu) {
+                // a touch that is alone on its coordinate: eqs. 3-5 on the spot
+                const bool earlier = (key[i][j] >> 30) & 1u;
+                const uint32_t sigma = earlier ? (key[i][j] >> 15) & 0x7fffu : 0u;  // what it had accumulated before the call
+                theta_of[i][c[i][j]] = step(th[i][j], sw.lr, sigma, v[i][j]);
+            } else {
+                const uint32_t pos = s_start[slot[j]] + atomicAdd(&s_fill[slot[j]], 1u);
+                s_key[pos] = key[i][j] | (is_nonzero(v[i][j]) ? 0x80000000u : 0u);
+                s_val[pos] = v[i][j];
+                s_theta[pos] = th[i][j];
+                s_coord[pos] = (uint16_t)c[i][j];
+                s_slot[pos] = (uint16_t)slot[j];
+            }
+        }
+        if (multi == 0) continue;  // uniform
+        __syncthreads();
+        // per touch on a shared coordinate: rank in time, sigma (eq. 3), alpha_k * value (eq. 5 and the multiply of eq. 4)
+        constexpr uint32_t MP = SP_MULTI / BLOCK;
+        float theta[MP];
+        uint32_t lo[MP], hi[MP], coord[MP];
+#pragma unroll
+        for (uint32_t j = 0; j < MP; ++j) {
+            const uint32_t x = tid + j * BLOCK;
+            lo[j] = hi[j] = 0;
+            if (x >= multi) continue;
+            const uint32_t kx = s_key[x], sx = s_slot[x];
+            const uint32_t qx = kx & 0x7fffu;
+            const bool earlier = (kx >> 30) & 1u;
+            const uint32_t field = (kx >> 15) & 0x7fffu;
+            const uint32_t pull = earlier ? 0u : qx - field;
+            const uint32_t beg = s_start[sx], end = s_start[sx + 1];
+            uint32_t rank = 0, sigma = earlier ? field : 0u;
+            for (uint32_t y = beg; y < end; ++y) {
+                const uint32_t ky = s_key[y];
+                const uint32_t qy = ky & 0x7fffu;
+                rank += qy < qx;
+                sigma += (ky >> 31) & (uint32_t)(qy >= pull && qy < qx);
+            }
+            float alpha = sw.lr;
+            if (sigma != 0) alpha = __fdiv_rn(sw.lr, (float)sigma);
+            s_prod[beg + rank] = __fmul_rn(alpha, s_val[x]);
+            if (rank == 0) {  // every touch of a coordinate fetched the same Theta; the earliest one folds
+                lo[j] = beg;
+                hi[j] = end;
+                coord[j] = s_coord[x];
+                theta[j] = s_theta[x];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t j = 0; j < MP; ++j) {  // eq. 4, in time order
+            if (hi[j] <= lo[j]) continue;
+            float t_k = theta[j];
+            for (uint32_t m = lo[j]; m < hi[j]; ++m) t_k = __fsub_rn(t_k, s_prod[m]);
+            theta_of[i][coord[j]] = t_k;
+        }
+    }
+}
+
 // The sweep for dense queues (about one queued entry per parameter or more).  There the lists
 // of a coordinate need no sorting: a tile is DTILE consecutive coordinates, thread c owns
 // coordinate c with Theta_c in a register, and the queue passes through LDS DQ updates at a
@@ -903,8 +1155,8 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_slow(Sweep sw) {
 // slice are requested before the current update is applied.
 __global__ __launch_bounds__(BLOCK) void k_sweep_hot(Sweep sw) {
     constexpr uint32_t QMAX = 64;
-    __shared__ float s_theta[TILE_MAX];
-    __shared__ uint64_t s_Z[TILE_MAX];
+    __shared__ float s_theta[HOT_TILE_MAX];
+    __shared__ uint64_t s_Z[HOT_TILE_MAX];
     __shared__ const uint32_t *s_idx[QMAX];
     __shared__ const float *s_valp[QMAX];
     __shared__ const uint32_t *s_pre[QMAX];
@@ -985,9 +1237,38 @@ __global__ __launch_bounds__(BLOCK) void k_sweep_hot(Sweep sw) {
 
 // ------------------------------------------------------------------ host side
 
+// Test hooks: environment switches that choose between execution plans with identical results.
+// They exist for tests and measurements, are read once at the start of a call, and are no part
+// of the interface.
+struct ApplyHooks {
+    enum Plan { AUTO, SCATTER, SWEEP } plan = AUTO;            // ADACOMP_APPLY_PLAN=scatter|sweep
+    enum Kernel { ANY, LONG, DENSE, TILED, SPARSE } kernel = ANY;  // ADACOMP_SWEEP_KERNEL=long|dense|tiled|sparse
+    uint32_t tpb = 0;                                          // ADACOMP_TPB=1|2|4 (0: the library's choice)
+};
+
+ApplyHooks read_apply_hooks() {
+    ApplyHooks hk;
+    if (const char *e = std::getenv("ADACOMP_APPLY_PLAN")) {
+        if (std::strcmp(e, "scatter") == 0) hk.plan = ApplyHooks::SCATTER;
+        else if (std::strcmp(e, "sweep") == 0) hk.plan = ApplyHooks::SWEEP;
+    }
+    if (const char *e = std::getenv("ADACOMP_SWEEP_KERNEL")) {
+        if (std::strcmp(e, "long") == 0) hk.kernel = ApplyHooks::LONG;
+        else if (std::strcmp(e, "dense") == 0) hk.kernel = ApplyHooks::DENSE;
+        else if (std::strcmp(e, "tiled") == 0) hk.kernel = ApplyHooks::TILED;
+        else if (std::strcmp(e, "sparse") == 0) hk.kernel = ApplyHooks::SPARSE;
+    }
+    if (const char *e = std::getenv("ADACOMP_TPB")) {
+        const int t = std::atoi(e);
+        hk.tpb = t == 4 || t == 2 ? (uint32_t)t : 1u;
+    }
+    return hk;
+}
+
 struct Layout {
     bool sweep = false;
     bool dense = false;   // sweep plan: one thread per coordinate (k_sweep_dense)
+    bool sparse = false;  // sweep plan: touches that are alone on their coordinate need no list (k_sweep_sparse)
     uint32_t tile_shift = 0;
     uint64_t ntiles = 0;
     uint32_t n_hist = 0;  // remembered updates this call reaches back to
@@ -1032,7 +1313,7 @@ int check_pulls(const adacomp_state_t *st, const adacomp_update_t *updates, uint
 // parameter plus about 30 per entry and three launches; the scatter about 440 bytes per entry
 // (measured line traffic) and one or two launches per update.
 void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_update_t *updates, uint32_t Q,
-                 Layout &lay) {
+                 const ApplyHooks &hk, Layout &lay) {
     double entries = 0, params = 0;
     bool fits32 = true;
     uint64_t oldest = t0;
@@ -1043,10 +1324,8 @@ void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_updat
     }
     lay.n_hist = (uint32_t)(t0 - oldest);
     for (uint32_t l = 0; l < L; ++l) params += (double)n[l];
-    // ADACOMP_APPLY_PLAN=scatter|sweep overrides the cost model (for tests and measurements)
-    const char *force = std::getenv("ADACOMP_APPLY_PLAN");
-    const bool never = force && std::strcmp(force, "scatter") == 0;
-    const bool always = force && std::strcmp(force, "sweep") == 0;
+    const bool never = hk.plan == ApplyHooks::SCATTER;  // the hooks override the cost model
+    const bool always = hk.plan == ApplyHooks::SWEEP;
     if (!never && Q >= 2 && Q <= 0x7fffu && fits32 && L > 0 && params > 0 && entries > 0) {
         // tile: about STAGE_CAP / 2 queued entries per tile on average, as long as the table of
         // slice bounds (Q x tiles) stays below twice the size of the updates themselves
@@ -1059,14 +1338,21 @@ void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_updat
         uint32_t shift = 0;
         while ((2u << shift) <= TILE_MAX) ++shift;  // log2(TILE_MAX)
         const double table_budget = std::max(64.0 * 1048576.0, 16.0 * entries);
-        // ADACOMP_SWEEP_KERNEL=dense|tiled overrides the choice between the two kinds of tile
-        const char *kind = std::getenv("ADACOMP_SWEEP_KERNEL");
-        const bool dense_forced = kind && std::strcmp(kind, "dense") == 0;
-        const bool dense_allowed = !kind || dense_forced;  // "tiled" and "long" name the sorting kernels
+        const bool dense_forced = hk.kernel == ApplyHooks::DENSE;
+        const bool dense_allowed = hk.kernel == ApplyHooks::ANY || dense_forced;  // the other names are those of the other kernels
         const bool dense = Q <= DENSE_QMAX && dense_allowed && (dense_forced || per_coord >= (Q <= 64 ? DENSE_PER_COORD : DENSE_PER_COORD_LONG)) &&
                            (dense_forced || 4.0 * (double)Q * (double)tiles_at(DTILE_SHIFT) <= table_budget);
+        // few entries per parameter, short queue: most touches are alone on their coordinate
+        const bool sparse = !dense && Q <= PASS_SHORT &&
+                            (hk.kernel == ApplyHooks::SPARSE || (hk.kernel == ApplyHooks::ANY && per_coord <= SPARSE_PER_COORD));
         if (dense) {
             shift = DTILE_SHIFT;
+        } else if (sparse) {
+            shift = 0;
+            while ((2u << shift) <= TILE_MAX_SPARSE) ++shift;  // log2(TILE_MAX_SPARSE)
+            while (shift > 0 && (double)(1u << shift) * per_coord > SP_CAP * 0.45 &&
+                   4.0 * (double)Q * (double)tiles_at(shift - 1) <= table_budget)
+                --shift;
         } else {
             while (shift > 0 && (double)(1u << shift) * per_coord > STAGE_CAP / 2 &&
                    4.0 * (double)Q * (double)tiles_at(shift - 1) <= table_budget)
@@ -1082,6 +1368,7 @@ void make_layout(const uint64_t *n, uint32_t L, uint64_t t0, const adacomp_updat
         if (ntiles < 0x7fffffffull && (always || scatter_cost > sweep_cost)) {
             lay.sweep = true;
             lay.dense = dense;
+            lay.sparse = sparse;
             lay.tile_shift = shift;
             lay.ntiles = ntiles;
         }
@@ -1139,7 +1426,7 @@ extern "C" int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adac
     rc = check_pulls(st, updates, Q);
     if (rc) return rc;
     Layout lay;
-    make_layout(n, L, st ? st->t : 0, updates, Q, lay);
+    make_layout(n, L, st ? st->t : 0, updates, Q, read_apply_hooks(), lay);
     *bytes = lay.bytes;
     return ADACOMP_OK;
 }
@@ -1180,8 +1467,9 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
     }
     rc = check_pulls(st, updates, Q);
     if (rc) return rc;
+    const ApplyHooks hk = read_apply_hooks();
     Layout lay;
-    make_layout(n.data(), L, t0, updates, Q, lay);
+    make_layout(n.data(), L, t0, updates, Q, hk, lay);
     if (!workspace || ((uintptr_t)workspace & 255u) || ws_bytes < lay.bytes) return ADACOMP_ERR_WORKSPACE;
     if (Q == 0) return ADACOMP_OK;
 
@@ -1290,13 +1578,13 @@ extern "C" int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, ad
             return ADACOMP_OK;
         }
         // several tiles per workgroup once there are enough tiles to fill the chip many times over
-        uint32_t tpb = lay.ntiles >= 65536 ? 4u : 1u;
-        if (const char *e = std::getenv("ADACOMP_TPB")) tpb = (uint32_t)std::atoi(e);
-        if (tpb != 4 && tpb != 2) tpb = 1;
+        const uint32_t tpb = hk.tpb ? hk.tpb : (lay.ntiles >= 65536 ? 4u : 1u);
         const dim3 grid((unsigned)((lay.ntiles + tpb - 1) / tpb));
-        const char *kind = std::getenv("ADACOMP_SWEEP_KERNEL");  // "long": the general kernel also for short queues
-        const bool short_queue = Q <= PASS_SHORT && !(kind && std::strcmp(kind, "long") == 0);
-        if (short_queue && tpb == 4) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_short<4>, grid, dim3(BLOCK), s, sw);
+        const bool short_queue = Q <= PASS_SHORT && hk.kernel != ApplyHooks::LONG;  // else the general kernel also for short queues
+        if (lay.sparse && tpb == 4) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_sparse<4>, grid, dim3(BLOCK), s, sw);
+        else if (lay.sparse && tpb == 2) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_sparse<2>, grid, dim3(BLOCK), s, sw);
+        else if (lay.sparse) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_sparse<1>, dim3((unsigned)lay.ntiles), dim3(BLOCK), s, sw);
+        else if (short_queue && tpb == 4) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_short<4>, grid, dim3(BLOCK), s, sw);
         else if (short_queue && tpb == 2) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_short<2>, grid, dim3(BLOCK), s, sw);
         else if (short_queue) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep_short<1>, dim3((unsigned)lay.ntiles), dim3(BLOCK), s, sw);
         else if (tpb == 4) ADACOMP_LAUNCH(ADACOMP_KERNEL_SWEEP, k_sweep<4>, grid, dim3(BLOCK), s, sw);

@@ -72,6 +72,7 @@ constexpr uint32_t SWAVES = SBLOCK / WAVE;
 // k_finish: one workgroup takes a tensor from the candidates its filter left to its output
 constexpr uint32_t FUSE_MAX_SEG = 2048;      // most segments of such a tensor (16.7M elements)
 constexpr uint32_t FUSE_MAX_CAND = 1u << 17; // ... and most candidates the plan expects for it (the kernel accepts twice as many)
+constexpr uint32_t FUSE_MAX_CAP = 320;       // ... and largest region: fuller segments are packed faster by the gather's many waves
 constexpr uint32_t FUSE_SHIFT = 11;          // key bits resolved by its second histogram; the first takes the 12 above
 constexpr uint32_t FUSE_SB = 16;             // segments whose candidate loads a wave has in flight together
 
@@ -295,7 +296,7 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
                 pack += slots;
                 cand_max = std::max(cand_max, cand);
                 ++grp.filters;
-                d.fused = hk.fused && d.nseg <= FUSE_MAX_SEG && m_est <= (double)FUSE_MAX_CAND;
+                d.fused = hk.fused && d.nseg <= FUSE_MAX_SEG && m_est <= (double)FUSE_MAX_CAND && d.cap <= FUSE_MAX_CAP;
                 if (d.fused) plan.any_fused = true;
                 else ++grp.unfused;
                 sblk += (d.npieces_s + SPIECES - 1) / SPIECES;
@@ -883,15 +884,12 @@ template <uint32_t GS>
 __global__ __launch_bounds__(BLOCK) void k_regather(Workspace ws) {
     const uint32_t n_redo = ws.redo[0];
     const uint32_t wave = threadIdx.x / WAVE;
-    for (uint32_t f = 0; f < n_redo; ++f) {
-        const uint32_t l = ws.redo[1 + f];
+    constexpr uint32_t NB = (FUSE_MAX_SEG + WAVES * GS - 1) / (WAVES * GS);  // workgroups' worth of segments of the largest such tensor
+    for (uint64_t g = blockIdx.x; g < (uint64_t)n_redo * NB; g += gridDim.x) {
+        const uint32_t l = ws.redo[1 + g / NB];
         const LayerDesc d = ws.desc[l];
-        if (ws.state[l].use_dense) continue;
-        const uint32_t nblk = (d.nseg + WAVES * GS - 1) / (WAVES * GS);
-        for (uint32_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
-            const uint32_t s0 = (blk * WAVES + wave) * GS;
-            if (s0 < d.nseg) gather_segments<GS>(ws, l, d, s0, true);
-        }
+        const uint32_t s0 = ((uint32_t)(g % NB) * WAVES + wave) * GS;
+        if (s0 < d.nseg && !ws.state[l].use_dense) gather_segments<GS>(ws, l, d, s0, true);
     }
 }
 

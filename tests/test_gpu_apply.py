@@ -628,7 +628,7 @@ def test_update_validate_and_malformed_entries_are_skipped(ac, dev, monkeypatch)
 
 
 @pytest.mark.parametrize("kernel,tpb", [("short", "1"), ("short", "2"), ("short", "4"), ("long", "1"), ("long", "2"), ("long", "4"),
-                                        ("dense", "1")])
+                                        ("dense", "1"), ("sparse", "1")])
 def test_sweep_kernels_and_tiles_per_workgroup(ac, dev, monkeypatch, kernel, tpb):
     """The sweep has a kernel for queues of up to 64 updates (all loads of a workgroup's tiles
     requested ahead) and a general one, each working through 1, 2 or 4 tiles per workgroup; forced
@@ -636,7 +636,7 @@ def test_sweep_kernels_and_tiles_per_workgroup(ac, dev, monkeypatch, kernel, tpb
     kernel, zero-valued entries and pulls that reach back across calls: always the oracle's result."""
     monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
     monkeypatch.setenv("ADACOMP_TPB", tpb)
-    monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", {"short": "tiled", "long": "long", "dense": "dense"}[kernel])
+    monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", {"short": "tiled", "long": "long", "dense": "dense", "sparse": "sparse"}[kernel])
     rng = np.random.default_rng(7 + int(tpb))
     sizes = [2048 * 5 + 3, 1, 0, 2048 * 2, 70_001]            # 6 + 1 + 0 + 2 + 35 tiles of 2048
     Q = 20
@@ -769,7 +769,7 @@ def test_degenerate_calls(ac, dev):
 
 @pytest.mark.parametrize("Q,density", [(2, 1.0), (17, 0.05), (33, 0.6), (64, 0.3), (64, 1.0), (65, 0.2), (130, 1.0), (200, 0.1),
                                        (256, 0.4)])
-@pytest.mark.parametrize("kernel", ["dense", "tiled"])
+@pytest.mark.parametrize("kernel", ["dense", "tiled", "sparse"])
 def test_dense_queues_one_thread_per_coordinate(ac, dev, monkeypatch, Q, density, kernel):
     """Queues with about one entry per parameter or more go through a sweep kernel of their own (a
     thread per coordinate, the non-zero touches of a coordinate as a bit mask over the queue) for
@@ -793,15 +793,16 @@ def test_dense_queues_one_thread_per_coordinate(ac, dev, monkeypatch, Q, density
         assert compare(got, want, f"{kernel}: Q={Q} density={density}, three calls with a trace") == 0
 
 
+@pytest.mark.parametrize("kernel", ["tiled", "sparse"])
 @pytest.mark.parametrize("Q", [10, 64, 70])
-def test_tiles_that_every_update_fills(ac, dev, monkeypatch, Q):
+def test_tiles_that_every_update_fills(ac, dev, monkeypatch, Q, kernel):
     """A sparse queue (large tiles) in which every update also carries one whole stretch of 3000
     consecutive parameters, as when the same rows are large in every worker's gradient: those tiles
     hold thousands of queued entries, slices of up to 2048 entries per update, and are replayed by
     the kernels for tiles that the sort declines (out of LDS up to 64 updates, from global memory
     beyond), in one call and in calls with a trace."""
     monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
-    monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", "tiled")
+    monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", kernel)
     rng = np.random.default_rng(500 + Q)
     sizes = [2048 * 12 + 77, 9]
     ups = random_updates(rng, sizes, Q, 0.002, zero_frac=0.1)
@@ -824,3 +825,52 @@ def test_tiles_that_every_update_fills(ac, dev, monkeypatch, Q):
     a = Q // 3
     got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev, chunks=[a, 2, Q - a - 2], history=Q)
     assert compare(got, want, f"filled tiles, Q={Q}, three calls with a trace") == 0
+
+
+@pytest.mark.parametrize("Q,density", [(16, 0.005), (2, 0.05), (40, 0.002), (64, 0.004), (16, 0.06)])
+def test_sparse_queues_lone_touches_need_no_list(ac, dev, monkeypatch, Q, density):
+    """The sweep for sparse queues applies a touch that is alone on its coordinate straight from
+    registers and groups only the touches of shared coordinates.  Forced here on ragged tensors of
+    several tiles with: a stretch of 200 coordinates that a third of the updates hit (a few hundred
+    entries on shared coordinates in one tile), a stretch of 400 coordinates that every update hits
+    (more shared entries than the kernel lists: the tile must be left untouched for the kernel for
+    overflowing tiles), a tile that collects more entries than the kernel stages at all,
+    zero-valued entries, and pulls that reach back across calls (lone touches then carry the
+    staleness accumulated before the call)."""
+    monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
+    monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", "sparse")
+    rng = np.random.default_rng(7000 + Q)
+    sizes = [4096 * 6 + 11, 1, 0, 4096 * 2, 90_001, 4097]
+    ups = random_updates(rng, sizes, Q, density, zero_frac=0.1)
+    some = np.arange(9000, 9200, dtype=np.uint32)        # tensor 0, tile 2
+    every = np.arange(17000, 17400, dtype=np.uint32)     # tensor 0, tile 4
+    full = np.arange(41000, 41000 + 1100, dtype=np.uint32)   # tensor 4, tile 10: 1100 entries from one update alone
+    for q in range(Q):
+        off, idx, val = ups[q]
+        parts_i, parts_v, new_off = [], [], [0]
+        for l in range(len(sizes)):
+            a, b = int(off[l]), int(off[l + 1])
+            ii = idx[a:b]
+            if l == 0:
+                ii = np.union1d(ii, every)
+                if q % 3 == 0:
+                    ii = np.union1d(ii, some)
+            if l == 4 and q == Q // 2:
+                ii = np.union1d(ii, full)
+            ii = ii.astype(np.uint32)
+            vv = rng.standard_normal(ii.size).astype(np.float32)
+            vv[rng.random(ii.size) < 0.1] = 0.0
+            parts_i.append(ii)
+            parts_v.append(vv)
+            new_off.append(new_off[-1] + ii.size)
+        ups[q] = (np.array(new_off, dtype=np.uint64), np.concatenate(parts_i), np.concatenate(parts_v))
+    pulls = [int(rng.integers(0, q + 1)) for q in range(Q)]
+    theta0 = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    want = run_oracle(theta0, ups, pulls, 0.02)
+    got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev)
+    assert st.t == Q
+    assert compare(got, want, f"sparse sweep, Q={Q} density={density}, one call") == 0
+    if Q >= 3:
+        a = Q // 3
+        got, _, st = run_gpu(ac, theta0, ups, pulls, 0.02, dev, chunks=[a, 1, Q - a - 1], history=Q)
+        assert compare(got, want, f"sparse sweep, Q={Q} density={density}, three calls with a trace") == 0
