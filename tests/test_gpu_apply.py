@@ -628,7 +628,7 @@ def test_update_validate_and_malformed_entries_are_skipped(ac, dev, monkeypatch)
 
 
 @pytest.mark.parametrize("kernel,tpb", [("short", "1"), ("short", "2"), ("short", "4"), ("long", "1"), ("long", "2"), ("long", "4"),
-                                        ("dense", "1"), ("sparse", "1")])
+                                        ("dense", "1"), ("sparse", "1"), ("sparse", "2"), ("sparse", "4")])
 def test_sweep_kernels_and_tiles_per_workgroup(ac, dev, monkeypatch, kernel, tpb):
     """The sweep has a kernel for queues of up to 64 updates (all loads of a workgroup's tiles
     requested ahead) and a general one, each working through 1, 2 or 4 tiles per workgroup; forced
@@ -827,8 +827,9 @@ def test_tiles_that_every_update_fills(ac, dev, monkeypatch, Q, kernel):
     assert compare(got, want, f"filled tiles, Q={Q}, three calls with a trace") == 0
 
 
+@pytest.mark.parametrize("tpb", ["1", "4"])
 @pytest.mark.parametrize("Q,density", [(16, 0.005), (2, 0.05), (40, 0.002), (64, 0.004), (16, 0.06)])
-def test_sparse_queues_lone_touches_need_no_list(ac, dev, monkeypatch, Q, density):
+def test_sparse_queues_lone_touches_need_no_list(ac, dev, monkeypatch, Q, density, tpb):
     """The sweep for sparse queues applies a touch that is alone on its coordinate straight from
     registers and groups only the touches of shared coordinates.  Forced here on ragged tensors of
     several tiles with: a stretch of 200 coordinates that a third of the updates hit (a few hundred
@@ -839,6 +840,7 @@ def test_sparse_queues_lone_touches_need_no_list(ac, dev, monkeypatch, Q, densit
     staleness accumulated before the call)."""
     monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
     monkeypatch.setenv("ADACOMP_SWEEP_KERNEL", "sparse")
+    monkeypatch.setenv("ADACOMP_TPB", tpb)
     rng = np.random.default_rng(7000 + Q)
     sizes = [4096 * 6 + 11, 1, 0, 4096 * 2, 90_001, 4097]
     ups = random_updates(rng, sizes, Q, density, zero_frac=0.1)
