@@ -13,7 +13,11 @@ experiments (211,690 parameters, 200 workers): a latency regime, reported the sa
 
 Prints ONE JSON line.  `roofline` is for the dominant kernel (select's streaming filter
 pass), timed live with HIP events on the launch stream inside the timed steps;
-`cpu_baseline` is the CPU oracle as it stands, single thread, on a bounded sample.
+`roofline_apply` is the same for the apply's kernels, `whole_path` prices the whole step
+by its algorithmic bytes, `per_gradient_calls` times the same step with one select call per
+worker gradient, `copy_ceiling_GBps` is what a plain device copy reaches on the same box;
+`cpu_baseline` is the CPU oracle as it stands on a bounded sample, on all host cores of
+the box's share (one tensor per thread) with the single-thread figure beside it.
 """
 import argparse
 import json
@@ -29,32 +33,49 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-def cpu_baseline(cfg, rate, lr, pulls, n_updates=16, layer=0):
-    """Oracle select + apply of `n_updates` worker updates: on one 10M-entry tensor of the flat
-    workload, on the whole model of the small one."""
-    import numpy as np
+def cpu_baseline(cfg, rate, lr, pulls, n_updates=8):
+    """Oracle select + apply of `n_updates` worker updates.  flat: on one 10M-entry tensor with one
+    thread, then on one tensor per thread with all cores of the box's share (tensors are independent
+    in both halves of the method); other workloads: the whole model, one thread."""
+    from concurrent.futures import ThreadPoolExecutor
 
     import oracle
     import workloads
 
+    def run(layers, n_up):
+        grads = [[workloads.gradient_layer(cfg, q, l).numpy() for l in layers] for q in range(n_up)]
+        theta = [t.numpy().copy() for t in workloads.theta0(cfg, layers=layers)]
+        ps = oracle.ParameterServer(theta)
+        t0 = time.perf_counter()
+        for q in range(n_up):
+            off, idx, val = oracle.select(grads[q], rate)
+            ps.apply(off, idx, val, min(pulls[q], q), lr)
+        return time.perf_counter() - t0, n_up * sum(g.size for g in grads[0])
+
     whole = cfg != "flat"
-    layers = list(range(len(workloads.sizes_of(cfg)))) if whole else [layer]
     if whole:     # about 1.6e8 elements through the oracle: 10 to 20 s
+        layers = list(range(len(workloads.sizes_of(cfg))))
         n_updates = max(1, min(len(pulls), int(1.6e8 // sum(workloads.sizes_of(cfg)))))
-    print(f"[bench] cpu baseline: oracle on {n_updates} updates", file=sys.stderr, flush=True)
-    grads = [[workloads.gradient_layer(cfg, q, l).numpy() for l in layers] for q in range(n_updates)]
-    theta = [t.numpy().copy() for t in workloads.theta0(cfg, layers=layers)]
-    ps = oracle.ParameterServer(theta)
+        print(f"[bench] cpu baseline: oracle on {n_updates} updates, 1 thread", file=sys.stderr, flush=True)
+        dt, elems = run(layers, n_updates)
+        return {"value": elems / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
+                "sample": f"{n_updates} worker updates of the whole model of the {cfg} workload "
+                          f"(select at {rate}, then PS apply), {dt:.1f} s of single-thread C"}
+    print(f"[bench] cpu baseline: oracle on {n_updates} updates of one tensor, 1 thread", file=sys.stderr, flush=True)
+    dt1, elems1 = run([0], n_updates)
+    cores = max(1, min(os.cpu_count() or 1, 16))     # the box's CPU share for one GPU
+    print(f"[bench] cpu baseline: the same on {cores} tensors, one per thread", file=sys.stderr, flush=True)
     t0 = time.perf_counter()
-    for q in range(n_updates):
-        off, idx, val = oracle.select(grads[q], rate)
-        ps.apply(off, idx, val, min(pulls[q], q), lr)
-    dt = time.perf_counter() - t0
-    elems = n_updates * sum(g.size for g in grads[0])
-    what = "the whole model" if whole else "one 10M-entry tensor"
-    return {"value": elems / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
-            "sample": f"{n_updates} worker updates of {what} of the {cfg} workload "
-                      f"(select at {rate}, then PS apply), {dt:.1f} s of single-thread C"}
+    with ThreadPoolExecutor(max_workers=cores) as ex:     # the C calls release the GIL
+        parts = list(ex.map(lambda l: run([l], n_updates), range(cores)))
+    dtc = time.perf_counter() - t0                        # includes generating the inputs: counted against the oracle
+    busy = max(p[0] for p in parts)
+    elems = sum(p[1] for p in parts)
+    return {"value": elems / busy, "unit": "elements/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_updates} worker updates of {cores} of the 100 10M-entry tensors of the flat workload, one tensor per "
+                      f"thread (select at {rate}, then PS apply): {busy:.1f} s in the slowest thread ({dtc:.1f} s with input "
+                      f"generation); one thread on one tensor: {elems1 / dt1:.3e} elements/s in {dt1:.1f} s",
+            "single_thread_value": elems1 / dt1}
 
 
 def main():
@@ -84,8 +105,8 @@ def main():
                          "comes from the same number of eager steps run afterwards)")
     ap.add_argument("--wire", action="store_true",
                     help="also encode / decode one worker update in the wire format and report bytes and times")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 4 GB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the device-copy ceiling and the per-gradient-call steps (flat workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -162,7 +183,7 @@ def main():
         ac.adacomp_apply(params, state, queue, lr, app_ws)
 
     copy_ceiling = None
-    if args.copy_calibration and cfg == "flat":     # reads 4e9 bytes, writes 4e9 bytes
+    if cfg == "flat" and not args.no_extras:     # a plain device copy: reads 4e9 bytes, writes 4e9 bytes
         src = torch.cat([g.view(-1) for g in grads[0]])
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
@@ -193,13 +214,13 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         t_end = time.perf_counter()
-        ac.adacomp_profile_start({dominant})
+        ac.adacomp_profile_start({dominant, "sweep", "bounds"})
         for _ in range(args.steps):
             step()
         torch.cuda.synchronize()
         prof = ac.adacomp_profile_stop()
     else:
-        ac.adacomp_profile_start({dominant})
+        ac.adacomp_profile_start({dominant, "sweep", "bounds"})
         t_begin = time.perf_counter()
         for _ in range(args.steps):
             step()
@@ -218,12 +239,31 @@ def main():
     launches_per_step = f_n / args.steps
     alg_bytes = Q * (4.0 * N + 8.0 * cap) / launches_per_step
     achieved = alg_bytes / f_avg_s / 1e9
-    traffic = None
+    traffic = apply_traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_flat.md")
     if os.path.exists(tpath) and cfg == "flat":   # HBM bytes per step from the committed rocprofv3 --pmc summary
         with open(tpath) as f:
-            m = re.search(r"k_filter HBM bytes per step:\s*(\d+)", f.read())
+            text = f.read()
+        m = re.search(r"k_filter HBM bytes per step:\s*(\d+)", text)
         traffic = float(m.group(1)) / launches_per_step if m else None
+        m = re.search(r"apply HBM bytes per step:\s*(\d+)", text)
+        apply_traffic = float(m.group(1)) if m else None
+    # the apply's kernels (slice bounds + sweep; the scatter plan has no such kernels): Sec. 4 "Complexity" counts
+    # work per received entry; algorithmic bytes per entry = 40 (index 4, value 4, Theta 4R + 4W, staleness
+    # bookkeeping 24), the figure the scope table states for the method, whatever plan executes it
+    apply_roof = None
+    if "sweep" in prof:
+        a_ms = (prof["sweep"][0] + prof.get("bounds", (0.0, 0))[0]) / prof["sweep"][1]
+        a_bytes = 40.0 * Q * cap
+        a_ach = a_bytes / (a_ms * 1e-3) / 1e9
+        apply_roof = {"bound": "hbm", "kernel": "k_bounds + sweep kernel (one launch each per queue)", "achieved": a_ach,
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a_ach / HBM_PEAK_GBS, "traffic": apply_traffic,
+                      "algorithmic_bytes_per_launch": a_bytes, "avg_launch_ms": a_ms, "launches": prof["sweep"][1],
+                      "bytes_per_entry": 40, "entries_per_launch": Q * cap}
+    whole_bytes = Q * (4.0 * N + 8.0 * cap) + 40.0 * Q * cap
+    whole = {"algorithmic_bytes_per_step": whole_bytes, "achieved_GBps": whole_bytes / (ms_per_step * 1e-3) / 1e9,
+             "frac_of_peak": whole_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+             "what": "select: 4 B per element read + 8 B per selected entry written; apply: 40 B per queued entry"}
     out = {
         "metric": "gradient elements/sec compressed+applied",
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -247,7 +287,10 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": 1e3 * f_avg_s,
                      "launches": f_n},
+        "whole_path": whole,
     }
+    if apply_roof:
+        out["roofline_apply"] = apply_roof
 
     # split of the step between the two halves (untimed extra steps, whole-call events)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -271,6 +314,38 @@ def main():
         out["kernels"] = kernels
     if copy_ceiling is not None:   # what a plain device copy of 4 GB reaches on this machine (read + write bytes per second)
         out["copy_ceiling_GBps"] = copy_ceiling
+        out["whole_path"]["frac_of_copy_ceiling"] = out["whole_path"]["achieved_GBps"] / copy_ceiling
+
+    if cfg == "flat" and batched and not args.no_extras:
+        # the same step with one adacomp_select call per worker gradient (a worker selects its own gradient):
+        # the small per-call kernels are then paid 16 times
+        pg_ws = torch.empty(ac.adacomp_select_workspace(sizes, rate), dtype=torch.uint8, device=dev)
+        pg_updates = [ac.Update(L, cap, dev) for _ in range(Q)]
+        pg_layers = [ac.Layers(g) for g in grads]
+        for q in range(Q):
+            ac.adacomp_select(pg_layers[q], rate, pg_updates[q], pg_ws)
+        pg_queue = ac.Queue(pg_updates)
+        pg_app_ws = torch.empty(max(256, ac.adacomp_apply_workspace(sizes, pg_updates)), dtype=torch.uint8, device=dev)
+
+        def pg_step():
+            t0 = state.t
+            for q in range(Q):
+                pg_updates[q].pull_ts = t0 + pulls[q]
+                ac.adacomp_select(pg_layers[q], rate, pg_updates[q], pg_ws)
+            ac.adacomp_apply(params, state, pg_queue, lr, pg_app_ws)
+
+        pg_steps = max(3, args.steps // 2)
+        for _ in range(2):
+            pg_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(pg_steps):
+            pg_step()
+        torch.cuda.synchronize()
+        pg_ms = 1e3 * (time.perf_counter() - t0) / pg_steps
+        out["per_gradient_calls"] = {"ms_per_step": pg_ms, "value": Q * N / (pg_ms * 1e-3), "unit": "elements/s",
+                                     "steps": pg_steps, "select_calls_per_step": Q}
+        del pg_ws, pg_updates, pg_layers, pg_queue, pg_app_ws
 
     if args.wire:      # one worker update (100 tensors x 50,000 entries) through the wire format and back
         u = updates[0]

@@ -127,6 +127,19 @@ struct LayerDesc {
 };
 static_assert(sizeof(LayerDesc) % 8 == 0, "descriptor table is uploaded as 64-bit words");
 
+// What the host uploads per tensor of the pipeline: a quarter of a LayerDesc.  Everything else in
+// the descriptor follows from these fields, the update's own offsets and prefix sums over the
+// tensors, which k_expand computes on the device (uploads travel in kernel-argument packets of
+// 3.5 KB: a call over 1600 tensors needs 11 of them this way instead of 43).
+struct CompactDesc {
+    const float *g;
+    uint32_t n;
+    uint32_t l;       // tensor number in the call: its count and output position are the update's offsets
+    uint32_t target;
+    uint32_t bits;    // mode (3 bits) | fused << 3 | first filtered tensor of a group << 4 | log2(stride) << 5 | cap << 8
+};
+static_assert(sizeof(CompactDesc) == 24, "table is uploaded as 64-bit words");
+
 struct LayerState {
     uint32_t t_lo;       // candidates are the entries with key >= t_lo
     uint32_t use_dense;  // descent and emit read the tensor itself, not the candidates
@@ -157,6 +170,7 @@ struct Workspace {
     uint32_t *pack_val;
     SmallEntry *small;    // [nsmall]
     uint32_t *redo;       // [L+1] redo[0] = number of tensors k_finish handed back, redo[1..] = their numbers
+    CompactDesc *compact; // [L]
     size_t bytes;
 };
 
@@ -171,6 +185,8 @@ struct Group {
 
 struct Plan {
     std::vector<LayerDesc> desc;  // the tensors that go through the pipeline, in order, then one entry with the totals
+    std::vector<uint32_t> number; // their numbers in the call
+    std::vector<char> opens;      // the tensor is the first filtered one of a group after the first
     std::vector<uint64_t> off;    // [L+1] first output entry of every tensor of the call
     std::vector<Group> groups;    // ranges of `desc`
     uint32_t gsegs = GSEGS;       // segments per wave in the gather
@@ -212,6 +228,8 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
               const uint64_t *k_override, const SelectHooks &hk, Plan &plan) {
     if (!(rate >= 0.0 && rate <= 1.0)) return ADACOMP_ERR_RATE;
     plan.desc.clear();
+    plan.number.clear();
+    plan.opens.clear();
     plan.off.assign((size_t)L + 1, 0);
     uint64_t seg = 0, cand = 0, out = 0, sblk = 0, wblk = 0, iblk = 0;
     // one workgroup per small tensor, if together they stay cache-sized
@@ -227,6 +245,7 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
         uint64_t k64 = k_override ? k_override[l] : adacomp_count(n[l], rate);
         if (k64 > n[l]) return ADACOMP_ERR_K_RANGE;
         LayerDesc d{};
+        bool opens = false;
         plan.off[l] = out;
         d.g = data ? data[l] : nullptr;
         d.n = (uint32_t)n[l];
@@ -289,6 +308,7 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
                     plan.groups.push_back(grp);
                     grp = Group{grp.l1, grp.l1, 0, 0};
                     cand = 0;
+                    opens = true;
                 }
                 d.cand_base = cand;
                 d.pack_base = pack;
@@ -305,7 +325,11 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
             wblk += (d.nseg + WAVES - 1) / WAVES;
         }
         // small and empty tensors never reach the pipeline's kernels: no descriptor, nothing to upload
-        if (d.mode != MODE_EMPTY && d.mode != MODE_SMALL) plan.desc.push_back(d);
+        if (d.mode != MODE_EMPTY && d.mode != MODE_SMALL) {
+            plan.desc.push_back(d);
+            plan.number.push_back(l);
+            plan.opens.push_back(opens);
+        }
         out += d.k;
     }
     // the gather's shape follows the fullest regions of the call
@@ -365,6 +389,7 @@ void carve(const Plan &plan, uint32_t L, void *base, Workspace &ws) {
     ws.pack_idx = (uint32_t *)take(plan.pack_total * sizeof(uint32_t));
     ws.pack_val = (uint32_t *)take(plan.pack_total * sizeof(uint32_t));
     ws.small = (SmallEntry *)take(plan.small.size() * sizeof(SmallEntry));
+    ws.compact = (CompactDesc *)take((size_t)L * sizeof(CompactDesc));
     ws.bytes = off;
 }
 
@@ -731,8 +756,8 @@ constexpr uint32_t CBLOCK = 1024, CITEMS = 4;
 
 // out[i] = load(0) + ... + load(i - 1) for i < n, by one workgroup of CBLOCK threads; returns the
 // total (the same in all threads).  `out` may be the array that `load` reads.
-template <class Load>
-__device__ __forceinline__ uint32_t scan_array(Load load, uint32_t *out, uint32_t n, uint32_t *s_wave) {
+template <class Load, class Store>
+__device__ __forceinline__ uint32_t scan_store(Load load, Store store, uint32_t n, uint32_t *s_wave) {
     uint32_t carry = 0;
     for (uint32_t i0 = 0; i0 < n; i0 += CBLOCK * CITEMS) {
         const uint32_t i = i0 + threadIdx.x * CITEMS;
@@ -746,12 +771,88 @@ __device__ __forceinline__ uint32_t scan_array(Load load, uint32_t *out, uint32_
         uint32_t run = carry + block_exclusive_scan<CBLOCK / WAVE>(sum, s_wave, total);
 #pragma unroll
         for (uint32_t j = 0; j < CITEMS; ++j) {
-            if (i + j < n) out[i + j] = run;
+            if (i + j < n) store(i + j, run);
             run += c[j];
         }
         carry += total;  // the callers' sums stay below 2^32
     }
     return carry;
+}
+
+template <class Load>
+__device__ __forceinline__ uint32_t scan_array(Load load, uint32_t *out, uint32_t n, uint32_t *s_wave) {
+    return scan_store(load, [&](uint32_t i, uint32_t v) { out[i] = v; }, n, s_wave);
+}
+
+// ---- descriptors from their compact form ----------------------------------------------
+// One workgroup: per tensor the fields that follow from its own size and count, then the
+// prefix sums over the tensors that place its segments, workgroups and candidates.
+__global__ __launch_bounds__(CBLOCK) void k_expand(Workspace ws, uint32_t L, const uint64_t *layer_off, uint32_t gsegs) {
+    __shared__ uint32_t s_wave[CBLOCK / WAVE];
+    __shared__ uint32_t s_carry;
+    for (uint32_t i = threadIdx.x; i < L; i += CBLOCK) {
+        const CompactDesc c = ws.compact[i];
+        LayerDesc d{};
+        d.g = c.g;
+        d.n = c.n;
+        d.out_off = layer_off[c.l];
+        d.k = (uint32_t)(layer_off[c.l + 1] - d.out_off);
+        d.mode = c.bits & 7u;
+        d.fused = (c.bits >> 3) & 1u;
+        d.stride = 1u << ((c.bits >> 5) & 7u);
+        d.cap = c.bits >> 8;
+        d.target = c.target;
+        d.vec = ((uintptr_t)c.g & 15u) == 0;
+        d.npieces = (uint32_t)(((uint64_t)c.n + PIECE - 1) / PIECE);
+        if (d.mode == MODE_FILTER) d.npieces_s = (d.npieces + d.stride - 1) / d.stride;
+        if (d.mode == MODE_FILTER || d.mode == MODE_DENSE) d.nseg = (uint32_t)(((uint64_t)c.n + WSEG - 1) / WSEG);
+        ws.desc[i] = d;
+    }
+    __syncthreads();
+    LayerDesc *D = ws.desc;
+    uint32_t tot;
+    tot = scan_store([&](uint32_t i) { return D[i].nseg; }, [&](uint32_t i, uint32_t v) { D[i].seg_base = v; }, L, s_wave);
+    if (threadIdx.x == 0) D[L].seg_base = tot;
+    tot = scan_store([&](uint32_t i) { return D[i].mode == MODE_FILTER ? (D[i].npieces_s + SPIECES - 1) / SPIECES : 0u; },
+                     [&](uint32_t i, uint32_t v) { D[i].sblk_base = v; }, L, s_wave);
+    if (threadIdx.x == 0) D[L].sblk_base = tot;
+    tot = scan_store([&](uint32_t i) { return (D[i].nseg + WAVES - 1) / WAVES; }, [&](uint32_t i, uint32_t v) { D[i].wblk_base = v; }, L, s_wave);
+    if (threadIdx.x == 0) D[L].wblk_base = tot;
+    tot = scan_store([&](uint32_t i) { return D[i].mode == MODE_IDENTITY ? (uint32_t)(((uint64_t)D[i].n + IDENT_TILE - 1) / IDENT_TILE) : 0u; },
+                     [&](uint32_t i, uint32_t v) { D[i].iblk_base = v; }, L, s_wave);
+    if (threadIdx.x == 0) D[L].iblk_base = tot;
+    tot = scan_store([&](uint32_t i) { return D[i].mode == MODE_FILTER ? (D[i].nseg + WAVES * gsegs - 1) / (WAVES * gsegs) : 0u; },
+                     [&](uint32_t i, uint32_t v) { D[i].gblk_base = v; }, L, s_wave);
+    if (threadIdx.x == 0) D[L].gblk_base = tot;
+    // candidate slots in units of 16 (a region is whole 128-byte lines): the packed arrays run through
+    // all tensors; the regions start again at 0 with every group
+    tot = scan_store([&](uint32_t i) { return D[i].mode == MODE_FILTER ? (uint32_t)((uint64_t)D[i].nseg * D[i].cap / 16) : 0u; },
+                     [&](uint32_t i, uint32_t v) { D[i].pack_base = 16ull * v; }, L, s_wave);
+    if (threadIdx.x == 0) D[L].pack_base = 16ull * tot;
+    __syncthreads();
+    // slots before the tensor's group: the running maximum of (slots before a tensor that opens a group)
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (uint32_t i0 = 0; i0 < L; i0 += CBLOCK) {
+        const uint32_t i = i0 + threadIdx.x;
+        const uint32_t lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+        const uint32_t before = i < L ? (uint32_t)(D[i].pack_base / 16) : 0u;
+        uint32_t m = i < L && ((ws.compact[i].bits >> 4) & 1u) ? before : 0u;
+#pragma unroll
+        for (int o = 1; o < WAVE; o <<= 1) {
+            const uint32_t y = __shfl_up(m, o);
+            if (lane >= (uint32_t)o && y > m) m = y;
+        }
+        if (lane == WAVE - 1) s_wave[wave] = m;
+        __syncthreads();
+        uint32_t prev = s_carry;
+        for (uint32_t w = 0; w < wave; ++w) prev = s_wave[w] > prev ? s_wave[w] : prev;
+        if (prev > m) m = prev;
+        if (i < L) D[i].cand_base = 16ull * (before - m);
+        __syncthreads();
+        if (threadIdx.x == CBLOCK - 1) s_carry = m;
+        __syncthreads();
+    }
 }
 
 // Whole workgroup.  Returns true if the packed candidates will be the source of the descent.
@@ -1923,8 +2024,20 @@ int select_impl(const adacomp_layer_t *layers, uint32_t L, double rate, const ui
         if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
     }
     if (tot.seg_base == 0 && tot.iblk_base == 0) return ADACOMP_OK;  // nothing for the pipeline
-    if (put_async(ws.desc, plan.desc.data(), plan.desc.size() * sizeof(LayerDesc), s) != hipSuccess)
-        return ADACOMP_ERR_HIP;
+    {
+        std::vector<CompactDesc> compact(Lp);
+        for (uint32_t i = 0; i < Lp; ++i) {
+            const LayerDesc &d = plan.desc[i];
+            uint32_t lg = 0;
+            while ((1u << lg) < d.stride) ++lg;
+            compact[i] = CompactDesc{d.g, d.n, plan.number[i], d.target,
+                                     d.mode | (d.fused << 3) | ((uint32_t)plan.opens[i] << 4) | (lg << 5) | (d.cap << 8)};
+        }
+        if (put_async(ws.compact, compact.data(), compact.size() * sizeof(CompactDesc), s) != hipSuccess)
+            return ADACOMP_ERR_HIP;
+        ADACOMP_LAUNCH(ADACOMP_KERNEL_PUT, k_expand, dim3(1), dim3(CBLOCK), s, ws, Lp, out->layer_off_dev, plan.gsegs);
+        if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
+    }
     if (tot.seg_base) {
         if (fill_u32_async(ws.hist, 0u, (size_t)Lp * BINS, s) != hipSuccess) return ADACOMP_ERR_HIP;
         LAUNCH(ADACOMP_KERNEL_SAMPLE_HIST, k_sample_hist, tot.sblk_base, ws, Lp);
