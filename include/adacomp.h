@@ -14,8 +14,9 @@
  * Conventions common to all calls
  *   - "DEVICE" pointers are HIP device memory of the current device, "HOST" pointers
  *     ordinary host memory.  Every buffer is allocated and owned by the caller; the
- *     library allocates no device memory, keeps no global state (the optional event
- *     timing at the end of this header aside) and never synchronises the device.
+ *     library allocates no device memory, keeps no global state (aside from the optional event
+ *     timing at the end of this header and the built-in scratch of adacomp_select_noalloc) and
+ *     never synchronises the device.
  *     All device work is enqueued on `hip_stream` (a hipStream_t passed as void*,
  *     NULL = the default stream) and is complete when that stream has drained.
  *     Host arrays are read before the call returns.
@@ -23,15 +24,13 @@
  *     checked before anything is enqueued: a failing call has no side effect.
  *   - Sizes are in elements unless a name says bytes.  A tensor has at most
  *     2^32 - 1 elements.  Zero-element tensors are legal.
- *   - Environment switches, read at every call; they choose between execution plans that
- *     give identical results and exist for tests and measurements:
- *       ADACOMP_APPLY_PLAN=scatter|sweep   force one plan of adacomp_apply
- *       ADACOMP_SWEEP_KERNEL=long          sweep plan: the general kernel also for queues of <= 64 updates
- *       ADACOMP_SWEEP_KERNEL=dense|tiled   sweep plan: always / never the kernel for dense queues (<= 256 updates)
- *       ADACOMP_TPB=1|2|4                  sweep plan: tiles per workgroup
- *       ADACOMP_SELECT_SMALL=0             small tensors take the streaming pipeline too
- *       ADACOMP_SELECT_GROUP_MB=<n>        candidate-region size per group of tensors (0: one group)
- *     The *_workspace call and the call it sizes must see the same values.
+ *   - Test hooks.  A few environment variables choose between execution plans that give
+ *     identical results (ADACOMP_APPLY_PLAN, ADACOMP_SWEEP_KERNEL, ADACOMP_TPB,
+ *     ADACOMP_SELECT_SMALL, ADACOMP_SELECT_FUSED, ADACOMP_SELECT_GROUP_MB).  They exist for the
+ *     library's own tests and measurements, are read once at the start of a call, and are not
+ *     part of this interface: leave them unset.  A *_workspace call and the call it sizes each
+ *     derive the plan from what they see; if a hook changes in between and the plan then needs
+ *     more bytes, the call is refused with ADACOMP_ERR_WORKSPACE.
  */
 #ifndef ADACOMP_H
 #define ADACOMP_H
@@ -210,9 +209,7 @@ int adacomp_apply_workspace(const uint64_t *n, uint32_t L, const adacomp_state_t
  *   lr       alpha, finite
  *   workspace DEVICE, 256-byte aligned, >= adacomp_apply_workspace() bytes
  * The queue is executed either update by update (scatter) or in one sweep over
- * coordinate tiles; the choice is made from the sizes and does not change the result.
- * The environment variable ADACOMP_APPLY_PLAN=scatter|sweep, read by this call and by
- * adacomp_apply_workspace, overrides it. */
+ * coordinate tiles; the choice is made from the sizes and does not change the result. */
 int adacomp_apply(const adacomp_param_layer_t *params, uint32_t L, adacomp_state_t *st,
                   const adacomp_update_t *updates, uint32_t Q, float lr,
                   void *workspace, size_t ws_bytes, void *hip_stream);

@@ -160,6 +160,62 @@ def test_apply_argument_checks_run_before_any_launch(lib):
     assert lib.adacomp_apply_workspace(n, 1, None, upd, 1, C.byref(need)) == -7
 
 
+def test_hook_flipped_between_sizing_and_call_is_caught(lib, monkeypatch):
+    """The environment switches are test hooks that choose between execution plans.  Both the sizing
+    call and the real call derive the plan and its workspace layout from what they see; if a hook
+    changes in between and the real call's plan needs more bytes than were sized, the call is
+    refused with ADACOMP_ERR_WORKSPACE before anything is enqueued."""
+    # select: small tensors are selected by one workgroup each and need next to no scratch; with the
+    # hook they go through the streaming pipeline (histograms, segment tables, candidate regions)
+    sizes = [200_000, 150_000, 70_000]
+    need_default = ac.adacomp_select_workspace(sizes, 0.01)
+    monkeypatch.setenv("ADACOMP_SELECT_SMALL", "0")
+    need_pipeline = ac.adacomp_select_workspace(sizes, 0.01)
+    assert need_pipeline > need_default
+    off = (C.c_uint64 * 4)()
+    layers = (binding._Layer * 3)()
+    for l, n in enumerate(sizes):
+        layers[l].data, layers[l].n = 0x100000 * (l + 1), n
+    upd = binding._Update(3, C.cast(off, C.POINTER(C.c_uint64)), 0x2000, 0x3000, 0x4000, sum(sizes), 0)
+    assert lib.adacomp_select(layers, 3, 0.01, None, C.byref(upd), 0x10000, need_default, None) == -5
+    monkeypatch.delenv("ADACOMP_SELECT_SMALL")
+    # the grouping hook only ever shrinks the candidate regions (groups reuse them): sized with one group, a call
+    # that sees several groups fits; sized with several groups, a call that sees one group is refused
+    big = [5_000_000] * 6
+    monkeypatch.setenv("ADACOMP_SELECT_GROUP_MB", "8")
+    need_groups = ac.adacomp_select_workspace(big, 0.01)
+    monkeypatch.setenv("ADACOMP_SELECT_GROUP_MB", "0")
+    need_one = ac.adacomp_select_workspace(big, 0.01)
+    assert need_one > need_groups
+    boff = (C.c_uint64 * 7)()
+    blayers = (binding._Layer * 6)()
+    for l, n in enumerate(big):
+        blayers[l].data, blayers[l].n = 0x10000000 * (l + 1), n
+    bupd = binding._Update(6, C.cast(boff, C.POINTER(C.c_uint64)), 0x2000, 0x3000, 0x4000, sum(big), 0)
+    assert lib.adacomp_select(blayers, 6, 0.01, None, C.byref(bupd), 0x10000, need_groups, None) == -5
+    monkeypatch.delenv("ADACOMP_SELECT_GROUP_MB")
+    # apply: the update-by-update plan needs the table and one snapshot word per entry, the sweep also
+    # the slice bounds of every update in every tile
+    n = (C.c_uint64 * 1)(3_000_000)
+    aoff = (C.c_uint64 * 2)(0, 30_000)
+    par = (binding._Layer * 1)()
+    par[0].data, par[0].n = 0x100000, 3_000_000
+    cnt = (C.c_void_p * 1)(0x5000000)
+    st = binding._State(0, 1, C.cast(cnt, C.POINTER(C.c_void_p)))
+    ups = (binding._Update * 8)()
+    for q in range(8):
+        ups[q] = binding._Update(1, C.cast(aoff, C.POINTER(C.c_uint64)), 0x2000, 0x300000, 0x400000, 30_000, 0)
+    need = C.c_size_t()
+    monkeypatch.setenv("ADACOMP_APPLY_PLAN", "scatter")
+    assert lib.adacomp_apply_workspace(n, 1, C.byref(st), ups, 8, C.byref(need)) == 0
+    need_scatter = need.value
+    monkeypatch.setenv("ADACOMP_APPLY_PLAN", "sweep")
+    assert lib.adacomp_apply_workspace(n, 1, C.byref(st), ups, 8, C.byref(need)) == 0
+    assert need.value > need_scatter
+    assert lib.adacomp_apply(par, 1, C.byref(st), ups, 8, 0.1, 0x10000, need_scatter, None) == -5
+    assert st.t == 0
+
+
 def test_wire_host_side_checks(lib):
     off = [0, 130, 130, 131]
     B = 3 + 0 + 1
