@@ -446,8 +446,11 @@ struct Source {
 };
 
 // Visit the elements [lo, hi) of a source with one wave, in order: the visitor is called
-// wave-wide once per 256-element piece with each lane holding 4 consecutive elements
+// wave-wide once per piece of up to 256 elements with each lane holding 4 consecutive elements
 // (idx[c], bits[c]); nvalid of them are inside the range.  WITH_IDX loads explicit indices.
+// A tensor that does not start on a 16-byte boundary (a view into a flat buffer) is read on the
+// aligned grid all the same: the up to 3 elements in front of the first boundary inside the
+// range make a short piece of their own, and the pieces after it are shifted by that much.
 template <bool WITH_IDX, bool STREAM = false, int NLOAD = 4, class F>
 __device__ __forceinline__ void visit_range(const Source &src, uint32_t lo, uint32_t hi, F &&f) {
     const uint32_t lane = threadIdx.x & (WAVE - 1);
@@ -456,7 +459,23 @@ __device__ __forceinline__ void visit_range(const Source &src, uint32_t lo, uint
     const bool with_idx = WITH_IDX && idxs != nullptr;
     constexpr uint32_t round = NLOAD * PIECE;  // elements per wave iteration: NLOAD 16-byte loads per lane in flight
     uint32_t r = lo;
-    if (src.vec) {
+    bool aligned = src.vec;  // element r of the source lies on a 16-byte boundary
+    if (!aligned && r < hi) {
+        const uint32_t mis = (uint32_t)((reinterpret_cast<uintptr_t>(vals) >> 2) & 3u);  // elements past a boundary at element 0
+        const uint32_t head = (4u - ((r + mis) & 3u)) & 3u;
+        if (head) {  // uniform
+            const uint32_t h_hi = hi - r > head ? r + head : hi;
+            const uint32_t first = r + lane * 4;
+            const uint4 v = load4<STREAM>(vals, first, h_hi, false);
+            uint32_t idx[4] = {first, first + 1, first + 2, first + 3};
+            const uint32_t bits[4] = {v.x, v.y, v.z, v.w};
+            const uint32_t nvalid = first >= h_hi ? 0u : (h_hi - first < 4u ? h_hi - first : 4u);
+            f(idx, bits, nvalid);
+            r = h_hi;
+        }
+        aligned = true;
+    }
+    if (aligned) {
         // whole rounds of an aligned source: plain vector loads, every element valid
         for (; hi - r >= round; r += round) {
             uint4 v[NLOAD], x[NLOAD];
@@ -485,10 +504,10 @@ __device__ __forceinline__ void visit_range(const Source &src, uint32_t lo, uint
     // position is advanced only while it stays below hi, it must not wrap)
     for (; r < hi; r = hi - r > PIECE ? r + PIECE : hi) {
         const uint32_t first = r + lane * 4;
-        const uint4 v = load4<STREAM>(vals, first, hi, src.vec);
+        const uint4 v = load4<STREAM>(vals, first, hi, aligned);
         uint32_t idx[4] = {first, first + 1, first + 2, first + 3};
         if (with_idx) {
-            const uint4 x = load4(idxs, first, hi, src.vec);
+            const uint4 x = load4(idxs, first, hi, true);
             idx[0] = x.x;
             idx[1] = x.y;
             idx[2] = x.z;
@@ -591,6 +610,11 @@ __global__ __launch_bounds__(BLOCK) void k_sample_hist(Workspace ws, uint32_t L)
     lds_hist_clear(h);
     const uint32_t p_lo = b * SPIECES;
     const uint32_t p_hi = p_lo + SPIECES < d.npieces_s ? p_lo + SPIECES : d.npieces_s;
+    // a tensor that does not start on a 16-byte boundary: a true sample (one piece in several) reads the
+    // 256 elements from the first boundary inside each sampled piece, so that the loads are 16 bytes wide
+    // (which elements are sampled does not matter to the result); a tensor read completely keeps its pieces
+    const uint32_t shift = (!d.vec && d.stride > 1) ? (4u - (uint32_t)((reinterpret_cast<uintptr_t>(d.g) >> 2) & 3u)) & 3u : 0u;
+    const bool wide = d.vec != 0 || shift != 0;
     uint32_t zero_run = 0;
     for (uint32_t p0 = p_lo + wave * 4; p0 < p_hi; p0 += WAVES * 4) {
         uint4 v[4];
@@ -604,8 +628,8 @@ __global__ __launch_bounds__(BLOCK) void k_sample_hist(Workspace ws, uint32_t L)
                 const uint64_t q = (uint64_t)p * d.stride + jit;
                 piece = q < d.npieces ? (uint32_t)q : d.npieces - 1;
             }
-            first[j] = piece * PIECE + lane * 4;
-            v[j] = load4(d.g, first[j], p < p_hi ? d.n : 0u, d.vec != 0);
+            first[j] = piece * PIECE + shift + lane * 4;
+            v[j] = load4(d.g, first[j], p < p_hi ? d.n : 0u, wide);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
