@@ -105,8 +105,9 @@ def main():
                          "comes from the same number of eager steps run afterwards)")
     ap.add_argument("--wire", action="store_true",
                     help="also encode / decode one worker update in the wire format and report bytes and times")
-    ap.add_argument("--no-extras", action="store_true",
-                    help="skip the device-copy ceiling and the per-gradient-call steps (flat workload)")
+    ap.add_argument("--no-copy-ceiling", action="store_true", help="skip the plain 4 GB device copy (flat workload)")
+    ap.add_argument("--no-per-gradient", action="store_true",
+                    help="skip the extra steps with one select call per worker gradient (flat workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -183,7 +184,7 @@ def main():
         ac.adacomp_apply(params, state, queue, lr, app_ws)
 
     copy_ceiling = None
-    if cfg == "flat" and not args.no_extras:     # a plain device copy: reads 4e9 bytes, writes 4e9 bytes
+    if cfg == "flat" and not args.no_copy_ceiling:     # a plain device copy: reads 4e9 bytes, writes 4e9 bytes
         src = torch.cat([g.view(-1) for g in grads[0]])
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
@@ -316,7 +317,7 @@ def main():
         out["copy_ceiling_GBps"] = copy_ceiling
         out["whole_path"]["frac_of_copy_ceiling"] = out["whole_path"]["achieved_GBps"] / copy_ceiling
 
-    if cfg == "flat" and batched and not args.no_extras:
+    if cfg == "flat" and batched and not args.no_per_gradient:
         # the same step with one adacomp_select call per worker gradient (a worker selects its own gradient):
         # the small per-call kernels are then paid 16 times
         pg_ws = torch.empty(ac.adacomp_select_workspace(sizes, rate), dtype=torch.uint8, device=dev)
