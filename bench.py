@@ -78,6 +78,48 @@ def cpu_baseline(cfg, rate, lr, pulls, n_updates=8):
             "single_thread_value": elems1 / dt1}
 
 
+def gpu_state(step, torch, busy_s=1.2, samples=4):
+    """Clocks, power and temperature of the card as rocm-smi reads them while untimed steps keep it busy:
+    the same binary runs a few per cent faster or slower from one box (one physical GPU) to the next."""
+    import subprocess
+    t_end = time.perf_counter() + busy_s
+    reads = []
+    while time.perf_counter() < t_end:
+        for _ in range(8):
+            step()          # asynchronous: the queue stays a few steps deep
+        try:
+            r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--showtemp", "--json"],
+                               capture_output=True, text=True, timeout=20)
+            card = next(iter(json.loads(r.stdout).values()))
+            reads.append(card)
+        except Exception:       # no rocm-smi, or output it cannot parse: the figure is context only
+            break
+        torch.cuda.synchronize()
+        if len(reads) >= samples:
+            break
+    torch.cuda.synchronize()
+    if not reads:
+        return None
+
+    def num(text):
+        m = re.search(r"-?\d+(\.\d+)?", str(text))
+        return float(m.group(0)) if m else None
+
+    out = {"samples": len(reads), "sampled_during": "untimed steps after the timed region"}
+    for key, name in (("sclk clock speed:", "sclk_MHz"), ("mclk clock speed:", "mclk_MHz"),
+                      ("Temperature (Sensor junction) (C)", "junction_C"), ("Temperature (Sensor memory) (C)", "memory_C")):
+        vals = [num(c.get(key)) for c in reads if num(c.get(key)) is not None]
+        if vals:
+            out[name] = {"min": min(vals), "max": max(vals)}
+    for c in reads:
+        for key, val in c.items():
+            if "ower" in key and "(W)" in key and num(val) is not None:
+                out.setdefault("power_W", {"min": num(val), "max": num(val)})
+                out["power_W"]["min"] = min(out["power_W"]["min"], num(val))
+                out["power_W"]["max"] = max(out["power_W"]["max"], num(val))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +148,7 @@ def main():
     ap.add_argument("--wire", action="store_true",
                     help="also encode / decode one worker update in the wire format and report bytes and times")
     ap.add_argument("--no-copy-ceiling", action="store_true", help="skip the plain 4 GB device copy (flat workload)")
+    ap.add_argument("--no-gpu-state", action="store_true", help="skip the rocm-smi readings under load (flat workload)")
     ap.add_argument("--no-per-gradient", action="store_true",
                     help="skip the extra steps with one select call per worker gradient (flat workload)")
     args = ap.parse_args()
@@ -347,6 +390,11 @@ def main():
         out["per_gradient_calls"] = {"ms_per_step": pg_ms, "value": Q * N / (pg_ms * 1e-3), "unit": "elements/s",
                                      "steps": pg_steps, "select_calls_per_step": Q}
         del pg_ws, pg_updates, pg_layers, pg_queue, pg_app_ws
+
+    if cfg == "flat" and not args.no_gpu_state:
+        st_ = gpu_state(step, torch)
+        if st_:
+            out["gpu_state"] = st_
 
     if args.wire:      # one worker update (100 tensors x 50,000 entries) through the wire format and back
         u = updates[0]
