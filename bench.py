@@ -5,7 +5,10 @@ Workload ("flat", the roofline configuration): a stream of 1B-element fp32 gradi
 queued worker updates with staleness uniform in [1,16].  One step = one pass of the
 whole path over one batch of 16 worker gradients, all resident in HBM: adacomp_select
 over all of them (one call over the 1600 tensors by default, or 16 calls with
---per-gradient-calls), then one adacomp_apply of the 16-update queue.
+--per-gradient-calls), then one adacomp_apply of the 16-update queue.  Three such batches
+(48 distinct worker gradients, 192 GB) stay resident and step i works on batch i mod 3: the
+stream is not one batch selected over and over, and the buffers span most of the HBM (the
+filter's speed depends on where its input lies, see profiles/filter_placement.md).
 value = gradient elements compressed and applied per second = 16e9 / step time.
 
 --workload paper_cnn runs the same step on the network size and worker count of the paper's own
@@ -120,6 +123,33 @@ def gpu_state(step, torch, busy_s=1.2, samples=4):
     return out
 
 
+def placement_experiment(ac, workloads, torch, dev, n_sets, rounds=3, steps=8):
+    """Same process, same call, different allocations: filter milliseconds per select call of 16e9 elements."""
+    cfg, rate, Q = "flat", 0.005, 16
+    sizes = workloads.sizes_of(cfg)
+    L = len(sizes)
+    cap = sum(ac.adacomp_count(n, rate) for n in sizes)
+    ws = torch.empty(ac.adacomp_select_workspace(sizes * Q, rate), dtype=torch.uint8, device=dev)
+    big = ac.Update(L * Q, cap * Q, dev)
+    sets = []
+    for i in range(n_sets):
+        grads = [workloads.gradient(cfg, 100 * i + q, device=dev) for q in range(Q)]
+        sets.append(ac.Layers([t for g in grads for t in g]))
+    res = []
+    for rnd in range(rounds):
+        for i, layers in enumerate(sets):
+            for _ in range(2):
+                ac.adacomp_select(layers, rate, big, ws)
+            torch.cuda.synchronize()
+            ac.adacomp_profile_start({"filter"})
+            for _ in range(steps):
+                ac.adacomp_select(layers, rate, big, ws)
+            torch.cuda.synchronize()
+            ms, launches = ac.adacomp_profile_stop()["filter"]
+            res.append({"round": rnd, "set": i, "filter_ms_per_call": ms / steps, "filter_launches_per_call": launches // steps})
+    print(json.dumps({"experiment": "placement", "sets": n_sets, "elements_per_call": Q * sum(sizes), "results": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -149,6 +179,13 @@ def main():
                     help="also encode / decode one worker update in the wire format and report bytes and times")
     ap.add_argument("--no-copy-ceiling", action="store_true", help="skip the plain 4 GB device copy (flat workload)")
     ap.add_argument("--no-gpu-state", action="store_true", help="skip the rocm-smi readings under load (flat workload)")
+    ap.add_argument("--batches", type=int, default=None,
+                    help="distinct batches of worker gradients kept resident; step i works on batch i mod this (default: 3 for "
+                         "flat = 48 gradients, 192 GB, so that the stream is not one batch selected over and over; 1 otherwise)")
+    ap.add_argument("--placement-sets", type=int, default=0,
+                    help="instead of the benchmark: allocate this many sets of 16 flat gradients (64 GB each) in one process, "
+                         "time the same select call on each set in turn, three rounds, and print the filter time per set: "
+                         "shows how much of the filter's run-to-run spread belongs to where the buffers lie in memory")
     ap.add_argument("--no-per-gradient", action="store_true",
                     help="skip the extra steps with one select call per worker gradient (flat workload)")
     args = ap.parse_args()
@@ -172,7 +209,16 @@ def main():
     L, N = len(sizes), sum(sizes)
     pulls = workloads.pull_timestamps(workloads.staleness(cfg))
 
-    grads = [workloads.gradient(cfg, q, device=dev, row_spread=args.row_spread, rows_shared=args.rows_shared) for q in range(Q)]      # 16 x 4 GB resident
+    if args.placement_sets > 0:
+        placement_experiment(ac, workloads, torch, dev, args.placement_sets)
+        return
+
+    nb = args.batches if args.batches else (3 if cfg == "flat" else 1)
+    # batch b holds the gradients of workers b*Q .. b*Q + Q-1 of the seeded stream: 16 x 4 GB resident per batch of flat
+    batches = [[workloads.gradient(cfg, b * Q + q, device=dev, row_spread=args.row_spread, rows_shared=args.rows_shared)
+                for q in range(Q)] for b in range(nb)]
+    grads = batches[0]
+    step_no = [0]
     theta = workloads.theta0(cfg, device=dev)
     state = ac.State(theta)
     cap = sum(ac.adacomp_count(n, rate) for n in sizes)
@@ -191,7 +237,8 @@ def main():
         # the C ABI takes any list of tensors: all 16 worker gradients (1600 tensors) go through ONE
         # select call, so the small per-call kernels are paid once; its output buffers are then
         # viewed as the 16 worker updates (100 tensors each, own pull timestamp) that apply takes
-        all_tensors = ac.Layers([t for g in grads for t in g])     # marshalled once
+        all_tensors_of = [ac.Layers([t for g in bt for t in g]) for bt in batches]     # marshalled once
+        all_tensors = all_tensors_of[0]
         big = ac.Update(L * Q, cap * Q, dev)
         sel_wss = [torch.empty(ac.adacomp_select_workspace(sizes * Q, rate), dtype=torch.uint8, device=dev)]
         ac.adacomp_select(all_tensors, rate, big, sel_wss[0])
@@ -205,10 +252,12 @@ def main():
 
     def selects():
         t0 = state.t
+        b = step_no[0] % nb        # the batch of worker gradients this step works on
+        step_no[0] += 1
         if batched:
             for q in range(Q):
                 updates[q].pull_ts = t0 + pulls[q]
-            ac.adacomp_select(all_tensors, rate, big, sel_wss[0])
+            ac.adacomp_select(all_tensors_of[b], rate, big, sel_wss[0])
             return
         # the 16 worker updates are independent: spread them over the streams, then join
         if ns > 1:
@@ -217,7 +266,7 @@ def main():
                 st.wait_event(ready)        # the previous apply has consumed the update buffers
         for q in range(Q):
             updates[q].pull_ts = t0 + pulls[q]
-            ac.adacomp_select(grads[q], rate, updates[q], sel_wss[q % ns], stream=streams[q % ns])
+            ac.adacomp_select(batches[b][q], rate, updates[q], sel_wss[q % ns], stream=streams[q % ns])
         if ns > 1:
             for st in streams:
                 main.wait_event(st.record_event())
@@ -326,6 +375,7 @@ def main():
                     "1 apply of the queue"),
                    "select_calls_per_step": 1 if batched else Q, "select_streams": ns, "hip_graph": bool(args.graph),
                    "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q,
+                   "resident_batches": nb, "resident_gradient_bytes": 4 * nb * Q * N,
                    "row_spread": args.row_spread, "rows_shared": bool(args.rows_shared)},
         "roofline": {"bound": "hbm", "kernel": "k_small" if small else "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -365,20 +415,22 @@ def main():
         # the small per-call kernels are then paid 16 times
         pg_ws = torch.empty(ac.adacomp_select_workspace(sizes, rate), dtype=torch.uint8, device=dev)
         pg_updates = [ac.Update(L, cap, dev) for _ in range(Q)]
-        pg_layers = [ac.Layers(g) for g in grads]
+        pg_layers_of = [[ac.Layers(g) for g in bt] for bt in batches]
         for q in range(Q):
-            ac.adacomp_select(pg_layers[q], rate, pg_updates[q], pg_ws)
+            ac.adacomp_select(pg_layers_of[0][q], rate, pg_updates[q], pg_ws)
         pg_queue = ac.Queue(pg_updates)
         pg_app_ws = torch.empty(max(256, ac.adacomp_apply_workspace(sizes, pg_updates)), dtype=torch.uint8, device=dev)
 
         def pg_step():
             t0 = state.t
+            b = step_no[0] % nb
+            step_no[0] += 1
             for q in range(Q):
                 pg_updates[q].pull_ts = t0 + pulls[q]
-                ac.adacomp_select(pg_layers[q], rate, pg_updates[q], pg_ws)
+                ac.adacomp_select(pg_layers_of[b][q], rate, pg_updates[q], pg_ws)
             ac.adacomp_apply(params, state, pg_queue, lr, pg_app_ws)
 
-        pg_steps = max(3, args.steps // 2)
+        pg_steps = max(nb, args.steps // 2 // nb * nb)
         for _ in range(2):
             pg_step()
         torch.cuda.synchronize()
@@ -389,7 +441,7 @@ def main():
         pg_ms = 1e3 * (time.perf_counter() - t0) / pg_steps
         out["per_gradient_calls"] = {"ms_per_step": pg_ms, "value": Q * N / (pg_ms * 1e-3), "unit": "elements/s",
                                      "steps": pg_steps, "select_calls_per_step": Q}
-        del pg_ws, pg_updates, pg_layers, pg_queue, pg_app_ws
+        del pg_ws, pg_updates, pg_layers_of, pg_queue, pg_app_ws
 
     if cfg == "flat" and not args.no_gpu_state:
         st_ = gpu_state(step, torch)
@@ -430,7 +482,7 @@ def main():
                        "unpack_GBps": (8.0 * cap + 4.0 * words) / (tm[1] * 1e-6) / 1e9}
 
     if not args.no_cpu_baseline:
-        del grads
+        del grads, batches
         out["cpu_baseline"] = cpu_baseline(cfg, rate, lr, pulls)
     print(json.dumps(out), flush=True)
 
