@@ -57,8 +57,10 @@ constexpr uint32_t DENSE_QMAX = 256;     // sweep plan: longest queue the kernel
 // ... and the queued entries per parameter from which it is used, for queues of up to 64 updates
 // and for longer ones (measured crossovers against the sorting kernels: 0.5-1.0 and 1.4-1.8)
 constexpr double DENSE_PER_COORD = 1.0, DENSE_PER_COORD_LONG = 1.75;
-// ... and the queued entries per parameter up to which the kernel for sparse queues is used
-constexpr double SPARSE_PER_COORD = 0.25;
+// ... and the queued entries per parameter up to which the kernel for sparse queues is used (measured against the
+// sorting kernel on the mid-size model, 64 updates: 0.19 entries per parameter 0.34 against 0.32 ms per queue, 0.64
+// entries per parameter 0.68 against 0.91 ms: its smaller table of slice bounds weighs more as the tiles shrink)
+constexpr double SPARSE_PER_COORD = 0.75;
 // one launch costs about as much as this many bytes of memory traffic (4 us at 5 TB/s)
 constexpr double LAUNCH_COST_BYTES = 20e6;
 static_assert((TILE_MAX & (TILE_MAX - 1)) == 0 && TILE_MAX >= BLOCK && STAGE_CAP % BLOCK == 0 && STAGE_CAP <= 65535,
