@@ -64,6 +64,7 @@ def test_cnn_repeatable_and_workspace_reuse(ac, dev):
         assert_update_equal(r, want, "repeat")
 
 
+@pytest.mark.fused_only
 @pytest.mark.parametrize("rate", [0.001, 0.01, 0.1])
 def test_mid_config(ac, dev, rate):
     """Config 'mid-size CNN': 57M Laplace gradients in 8 tensors."""
@@ -372,6 +373,7 @@ def _sampled_pieces(n):
     return np.minimum(p * stride + jit, npieces - 1), stride
 
 
+@pytest.mark.fused_only
 @pytest.mark.parametrize("bias,what", [(1.12, "the reserve threshold takes over"), (1.6, "the tensor itself is read"),
                                        (0.8, "more candidates than needed")])
 def test_sample_that_misjudges_the_threshold(ac, dev, bias, what):
