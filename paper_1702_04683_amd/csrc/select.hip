@@ -74,7 +74,7 @@ constexpr uint32_t FUSE_MAX_SEG = 2048;      // most segments of such a tensor (
 constexpr uint32_t FUSE_MAX_CAND = 1u << 17; // ... and most candidates the plan expects for it (the kernel accepts twice as many)
 constexpr uint32_t FUSE_MAX_CAP = 320;       // ... and largest region: fuller segments are packed faster by the gather's many waves
 constexpr uint32_t FUSE_SHIFT = 11;          // key bits resolved by its second histogram; the first takes the 12 above
-constexpr uint32_t FUSE_SB = 16;             // segments whose candidate loads a wave has in flight together
+constexpr uint32_t FUSE_ROWS = 16;           // rows of 64 candidates that a packing wave of k_finish has in flight
 
 // Candidate regions of one group of tensors: consecutive tensors are filtered and finished (or
 // checked and packed) together, and the next group reuses the same region memory.  About a fifth
@@ -1392,10 +1392,11 @@ __global__ __launch_bounds__(SBLOCK) void k_small(const SmallEntry *S, const uin
 // megabyte that the filter of its group has just written and that is still in cache.  One
 // workgroup per tensor, launched right after that filter, takes it from there to its output with
 // no further launches:
-//   pack     every wave copies the regions of a contiguous range of segments to the packed arrays,
-//            in index order (a segment whose region overflowed is read from the tensor and filtered
-//            again), and bins (key - t_lo) >> 11 into 4096 bins (keys a factor two or more above
-//            t_lo share the last bin) -> the bin of the k-th largest key;
+//   pack     the regions' candidates are copied to the packed arrays in index order: every wave fills
+//            an even share of the packed positions (whole rows of 64), gathering each row from the
+//            regions it falls into (a segment whose region overflowed is read from the tensor and
+//            filtered again), and bins (key - t_lo) >> 11 into 4096 bins (keys a factor two or more
+//            above t_lo share the last bin) -> the bin of the k-th largest key;
 //   level 2  histogram of the low 11 bits inside that bin over the packed candidates -> the exact
 //            threshold key T and the tie quota r;
 //   count    every wave counts key > T and key == T in its even share of the packed candidates;
@@ -1413,39 +1414,27 @@ __global__ __launch_bounds__(SBLOCK) void k_finish(Workspace ws, uint32_t l0, ui
     static_assert(SBLOCK == CBLOCK, "the check and the finish share a workgroup");
     static_assert(ESTAGE > PIECE && ESTAGE * 2 * SWAVES >= BINS, "emit buffer: more than a piece; it shares LDS with the histogram");
     __shared__ uint32_t s_buf[2 * ESTAGE * SWAVES];  // first the histogram, then the waves' emit buffers (index, value)
-    __shared__ uint16_t s_cnt[FUSE_MAX_SEG];
+    __shared__ uint32_t s_pre[FUSE_MAX_SEG + 1];  // packed position of each segment's first candidate; [nseg] = all
     __shared__ uint32_t s_wave[SWAVES];
-    __shared__ uint32_t s_first[SWAVES], s_gt[SWAVES], s_eq[SWAVES];
+    __shared__ uint32_t s_gt[SWAVES], s_eq[SWAVES];
     __shared__ uint32_t s_res[2];
     uint32_t *s_hist = s_buf;
     const uint32_t l = l0 + blockIdx.x;
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER) return;
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wv = tid / WAVE;
-    const uint32_t per = (d.nseg + SWAVES - 1) / SWAVES;  // segments per wave
+    const uint32_t per = (d.nseg + SWAVES - 1) / SWAVES;  // segments per wave (for the segments that overflowed)
     const uint32_t s_lo = wv * per < d.nseg ? wv * per : d.nseg;
     const uint32_t s_hi = s_lo + per < d.nseg ? s_lo + per : d.nseg;
     bool take = d.fused != 0;
     uint32_t m = 0;
     if (take) {
-        // counts of all segments into LDS; candidates per wave and in all
+        // packed position of every segment's first candidate = prefix sums of the counts, in LDS
         const uint32_t *cnt = ws.seg_cnt + d.seg_base;
-        for (uint32_t i = tid; i < d.nseg; i += SBLOCK) s_cnt[i] = (uint16_t)cnt[i];  // at most WSEG
         for (uint32_t i = tid; i < BINS; i += SBLOCK) s_hist[i] = 0;
+        m = scan_store([&](uint32_t i) { return cnt[i]; }, [&](uint32_t i, uint32_t v) { s_pre[i] = v; }, d.nseg, s_wave);
+        if (tid == 0) s_pre[d.nseg] = m;
         __syncthreads();
-        uint32_t mine = 0;  // this wave's candidates (wave-uniform after the reduction)
-        for (uint32_t i = s_lo + lane; i < s_hi; i += WAVE) mine += s_cnt[i];
-#pragma unroll
-        for (int o = WAVE / 2; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
-        if (lane == 0) s_first[wv] = mine;
-        __syncthreads();
-        uint32_t first = 0;
-        for (uint32_t w = 0; w < SWAVES; ++w) {
-            if (w < wv) first += s_first[w];
-            m += s_first[w];
-        }
-        __syncthreads();
-        if (lane == 0) s_first[wv] = first;  // packed position of the wave's first candidate
         const uint64_t room = std::min<uint64_t>((uint64_t)d.nseg * d.cap, d.n / 4);
         take = m >= d.k && m <= 2 * FUSE_MAX_CAND && m <= room;
     }
@@ -1462,74 +1451,104 @@ __global__ __launch_bounds__(SBLOCK) void k_finish(Workspace ws, uint32_t l0, ui
     const uint32_t t_lo = ws.state[l].t_lo;
     uint32_t *__restrict__ pidx = ws.pack_idx + d.pack_base;
     uint32_t *__restrict__ pval = ws.pack_val + d.pack_base;
+    // the wave's even share of the packed candidates, in whole pieces
+    const uint32_t share = ((m + SWAVES - 1) / SWAVES + PIECE - 1) / PIECE * PIECE;
+    const uint32_t wv_u = __builtin_amdgcn_readfirstlane(wv);  // tells the compiler that the share is wave-uniform
+    const uint32_t c_lo = wv_u * share < m ? wv_u * share : m;
+    const uint32_t c_hi = m - c_lo < share ? m : c_lo + share;
     {   // pack + first histogram
         const uint2 *__restrict__ regions = ws.cand + d.cand_base;
-        const Source dense{reinterpret_cast<const uint32_t *>(d.g), nullptr, d.n, WSEG, d.vec != 0};
+        const uint32_t cap = d.cap;
         auto bin_of = [&](uint32_t bits) {
             const uint32_t b = (mag_key(bits) - t_lo) >> FUSE_SHIFT;
             return b < BINS - 1 ? b : BINS - 1;
         };
-        uint32_t pos = s_first[wv];  // wave-uniform
-        for (uint32_t s0 = s_lo; s0 < s_hi; s0 += FUSE_SB) {
-            uint32_t cnt[FUSE_SB];
-            uint2 a[FUSE_SB];
-            uint32_t over = 0;  // segments of the batch whose region overflowed (bit j)
-#pragma unroll
-            for (uint32_t j = 0; j < FUSE_SB; ++j) {
-                cnt[j] = s0 + j < s_hi ? __builtin_amdgcn_readfirstlane((uint32_t)s_cnt[s0 + j]) : 0u;
-                if (cnt[j] > d.cap) over |= 1u << j;
-                else if (lane < cnt[j]) a[j] = regions[(uint64_t)(s0 + j) * d.cap + lane];
+        // Packed position c belongs to the segment seg with s_pre[seg] <= c < s_pre[seg + 1] and is entry
+        // c - s_pre[seg] of its region.  A lane visits the positions c_lo + lane, + 64, ...: it looks its
+        // first segment up by bisection and walks on from there.  Each row of 64 positions is one gather
+        // from two or three regions and two full-width stores; FUSE_ROWS rows are requested, then stored.
+        // Positions of a segment whose region overflowed are left out here.
+        const uint32_t rows = (c_hi - c_lo + WAVE - 1) / WAVE;  // wave-uniform
+        uint32_t seg = 0;
+        {
+            const uint32_t c0 = c_lo + lane < m ? c_lo + lane : m - 1;  // m >= k >= 1
+            uint32_t hi = d.nseg;
+            while (hi - seg > 1) {
+                const uint32_t mid = (seg + hi) / 2;
+                if (s_pre[mid] <= c0) seg = mid;
+                else hi = mid;
             }
-            const uint32_t pos0 = pos;
-#pragma unroll
-            for (uint32_t j = 0; j < FUSE_SB; ++j) {
-                if (cnt[j] <= d.cap) {  // uniform
-                    if (lane < cnt[j]) {
-                        pidx[pos + lane] = a[j].x;
-                        pval[pos + lane] = a[j].y;
-                        atomicAdd(&s_hist[bin_of(a[j].y)], 1u);
-                    }
-                    for (uint32_t e = WAVE + lane; e < cnt[j]; e += WAVE) {
-                        const uint2 c = regions[(uint64_t)(s0 + j) * d.cap + e];
-                        pidx[pos + e] = c.x;
-                        pval[pos + e] = c.y;
-                        atomicAdd(&s_hist[bin_of(c.y)], 1u);
-                    }
+        }
+        uint32_t base = s_pre[seg], lim = s_pre[seg + 1];
+        uint2 a[FUSE_ROWS];
+        uint32_t have = 0;  // bit j: a[j] holds a candidate
+        // Every lane loads in every slot, from entry 0 of the first region where it has nothing to fetch:
+        // only when the number of loads issued after a given one is known at compile time can the wait
+        // for that one leave the later ones in flight.
+        auto request = [&](uint32_t j, uint32_t row) {
+            const uint32_t c = c_lo + row * WAVE + lane;
+            uint64_t at = 0;
+            bool real = false;
+            if (c < c_hi) {
+                while (c >= lim) {  // ends: c < m = s_pre[nseg]
+                    ++seg;
+                    base = lim;
+                    lim = s_pre[seg + 1];
                 }
-                pos += cnt[j];
+                if (lim - base <= cap) {
+                    at = (uint64_t)seg * cap + (c - base);
+                    real = true;
+                }
             }
-            if (over) {  // those regions hold only the first `cap` candidates: filter the segments again
-                uint32_t p0 = pos0;
-#pragma unroll 1
-                for (uint32_t j = 0; j < FUSE_SB && s0 + j < s_hi; ++j) {
-                    const uint32_t c_j = __builtin_amdgcn_readfirstlane((uint32_t)s_cnt[s0 + j]);
-                    if ((over >> j) & 1u) {
-                        const uint32_t lo = (s0 + j) * WSEG;
-                        const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
-                        uint32_t q0 = p0;
-                        visit_range<false, false, 4>(dense, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
-                            bool f[4];
-                            uint64_t mk[4];
+            a[j] = regions[at];
+            have = real ? have | (1u << j) : have & ~(1u << j);
+        };
+        auto retire = [&](uint32_t j, uint32_t row) {
+            if ((have >> j) & 1u) {
+                const uint32_t c = c_lo + row * WAVE + lane;
+                pidx[c] = a[j].x;
+                pval[c] = a[j].y;
+                atomicAdd(&s_hist[bin_of(a[j].y)], 1u);
+            }
+        };
+        for (uint32_t row0 = 0; row0 < rows; row0 += FUSE_ROWS) {
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                f[c] = (uint32_t)c < nvalid && mag_key(bits[c]) >= t_lo;
-                                mk[c] = __ballot(f[c]);
-                            }
-                            uint32_t p = q0 + lanes_below(mk[0]) + lanes_below(mk[1]) + lanes_below(mk[2]) + lanes_below(mk[3]);
+            for (uint32_t j = 0; j < FUSE_ROWS; ++j) request(j, row0 + j);
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                if (f[c]) {
-                                    pidx[p] = idx[c];
-                                    pval[p] = bits[c];
-                                    atomicAdd(&s_hist[bin_of(bits[c])], 1u);
-                                    ++p;
-                                }
-                            }
-                            q0 += popc64(mk[0]) + popc64(mk[1]) + popc64(mk[2]) + popc64(mk[3]);
-                        });
+            for (uint32_t j = 0; j < FUSE_ROWS; ++j) retire(j, row0 + j);
+        }
+        // a region that overflowed holds only its first `cap` candidates: the wave filters such a segment
+        // of its range of segments again, from the tensor, to the segment's packed positions
+        const Source dense{reinterpret_cast<const uint32_t *>(d.g), nullptr, d.n, WSEG, d.vec != 0};
+        for (uint32_t s0 = s_lo; s0 < s_hi; s0 += WAVE) {
+            const uint32_t sg = s0 + lane;
+            uint64_t over = __ballot(sg < s_hi && s_pre[sg + 1] - s_pre[sg] > cap);
+            while (over) {  // uniform
+                const uint32_t os = s0 + (uint32_t)__builtin_ctzll(over);
+                over &= over - 1;
+                const uint32_t lo = os * WSEG;
+                const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
+                uint32_t q0 = s_pre[os];
+                visit_range<false, false, 4>(dense, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
+                    bool f[4];
+                    uint64_t mk[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        f[c] = (uint32_t)c < nvalid && mag_key(bits[c]) >= t_lo;
+                        mk[c] = __ballot(f[c]);
                     }
-                    p0 += c_j;
-                }
+                    uint32_t p = q0 + lanes_below(mk[0]) + lanes_below(mk[1]) + lanes_below(mk[2]) + lanes_below(mk[3]);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        if (f[c]) {
+                            pidx[p] = idx[c];
+                            pval[p] = bits[c];
+                            atomicAdd(&s_hist[bin_of(bits[c])], 1u);
+                            ++p;
+                        }
+                    }
+                    q0 += popc64(mk[0]) + popc64(mk[1]) + popc64(mk[2]) + popc64(mk[3]);
+                });
             }
         }
     }
@@ -1545,11 +1564,7 @@ __global__ __launch_bounds__(SBLOCK) void k_finish(Workspace ws, uint32_t l0, ui
         }
         return;
     }
-    // the wave's even share of the packed candidates, in whole pieces
     const Source packed{pval, pidx, m, VCHUNK, true};
-    const uint32_t share = ((m + SWAVES - 1) / SWAVES + PIECE - 1) / PIECE * PIECE;
-    const uint32_t c_lo = wv * share < m ? wv * share : m;
-    const uint32_t c_hi = m - c_lo < share ? m : c_lo + share;
     for (uint32_t i = tid; i < (1u << FUSE_SHIFT); i += SBLOCK) s_hist[i] = 0;
     __syncthreads();
     visit_range<false, false, 4>(packed, c_lo, c_hi, [&](const uint32_t(&)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
