@@ -8,7 +8,10 @@ over all of them (one call over the 1600 tensors by default, or 16 calls with
 --per-gradient-calls), then one adacomp_apply of the 16-update queue.  Three such batches
 (48 distinct worker gradients, 192 GB) stay resident and step i works on batch i mod 3: the
 stream is not one batch selected over and over, and the buffers span most of the HBM (the
-filter's speed depends on where its input lies, see profiles/filter_placement.md).
+filter's speed depends on where its input lies, see profiles/filter_placement.md).  For the
+same reason the run waits 20 s before it touches the GPU (--settle): buffers allocated within
+seconds of another process releasing as many land differently in the card's memory and are
+read 7 % slower for the life of the process (profiles/filter_after_idle.md).
 value = gradient elements compressed and applied per second = 16e9 / step time.
 
 --workload paper_cnn runs the same step on the network size and worker count of the paper's own
@@ -188,9 +191,17 @@ def main():
                          "shows how much of the filter's run-to-run spread belongs to where the buffers lie in memory")
     ap.add_argument("--no-per-gradient", action="store_true",
                     help="skip the extra steps with one select call per worker gradient (flat workload)")
+    ap.add_argument("--settle", type=float, default=None,
+                    help="seconds to wait before anything touches the GPU (default: 20 for flat, 0 otherwise). A process "
+                         "that allocates its 200 GB within seconds of another one releasing as much gets them placed "
+                         "differently in the card's memory, and the streaming read is then 7 %% slower for the life of "
+                         "the process; after 20 s of idle the placement is that of a fresh machine")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+    settle_s = args.settle if args.settle is not None else (20.0 if args.workload == "flat" else 0.0)
+    if settle_s > 0:
+        time.sleep(settle_s)
 
     import torch
 
@@ -375,7 +386,7 @@ def main():
                     "1 apply of the queue"),
                    "select_calls_per_step": 1 if batched else Q, "select_streams": ns, "hip_graph": bool(args.graph),
                    "elements_per_step": Q * N, "entries_per_update": cap, "queue": Q,
-                   "resident_batches": nb, "resident_gradient_bytes": 4 * nb * Q * N,
+                   "resident_batches": nb, "resident_gradient_bytes": 4 * nb * Q * N, "settle_s": settle_s,
                    "row_spread": args.row_spread, "rows_shared": bool(args.rows_shared)},
         "roofline": {"bound": "hbm", "kernel": "k_small" if small else "k_filter", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
