@@ -201,6 +201,7 @@ def main():
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
     settle_s = args.settle if args.settle is not None else (20.0 if args.workload == "flat" else 0.0)
     if settle_s > 0:
+        print(f"[bench] idling {settle_s:g} s before the first GPU allocation (--settle)", file=sys.stderr, flush=True)
         time.sleep(settle_s)
 
     import torch
