@@ -405,6 +405,29 @@ __device__ __forceinline__ uint32_t find_layer(const LayerDesc *d, uint32_t L, u
     return lo;
 }
 
+// The same among the tensors [lo, hi) when d[lo].*BASE <= blk < d[hi].*BASE (d[hi] exists: the table
+// ends with an entry of totals).  The first probe is placed by proportion, which is the answer when
+// the tensors of the range are equally large: two rounds of loads instead of log2(L) dependent ones
+// in front of a workgroup's first data load.  Any other layout falls through to the bisection.
+template <uint32_t LayerDesc::*BASE>
+__device__ __forceinline__ uint32_t find_layer_in(const LayerDesc *d, uint32_t lo, uint32_t hi, uint32_t blk) {
+    const uint32_t b_lo = d[lo].*BASE, b_hi = d[hi].*BASE;
+    uint32_t g = lo + (uint32_t)((float)(blk - b_lo) * (float)(hi - lo) / (float)(b_hi - b_lo));
+    if (g >= hi) g = hi - 1;
+    const uint32_t b_g = d[g].*BASE, b_next = d[g + 1].*BASE;
+    if (b_g <= blk) {
+        if (b_next > blk) return g;
+        lo = g + 1;  // d[g + 1].*BASE <= blk
+    } else {
+        hi = g;
+    }
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (d[mid].*BASE <= blk) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Tensor pointers come out of descriptor tables in memory, so the compiler cannot tell that
@@ -603,7 +626,7 @@ __device__ __forceinline__ void lds_hist_add(uint32_t *h, const uint32_t (&key)[
 // ---- step 1: sample histogram on the top 12 key bits -----------------------------
 __global__ __launch_bounds__(BLOCK) void k_sample_hist(Workspace ws, uint32_t L) {
     __shared__ uint32_t h[BINS];
-    const uint32_t l = find_layer<&LayerDesc::sblk_base>(ws.desc, L, blockIdx.x);
+    const uint32_t l = find_layer_in<&LayerDesc::sblk_base>(ws.desc, 0, L, blockIdx.x);
     const LayerDesc d = ws.desc[l];
     const uint32_t b = blockIdx.x - d.sblk_base;
     const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
@@ -704,10 +727,10 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_wave_barrier();
 }
 
-__global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t L, uint32_t blk0) {
+__global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t l0, uint32_t l1, uint32_t blk0) {
     __shared__ uint2 s_stage[WAVES][FSTAGE];
-    const uint32_t blk = blk0 + blockIdx.x;  // workgroup number across all groups of tensors
-    const uint32_t l = find_layer<&LayerDesc::wblk_base>(ws.desc, L, blk);
+    const uint32_t blk = blk0 + blockIdx.x;  // workgroup number across all groups of tensors; the launch covers tensors [l0, l1)
+    const uint32_t l = find_layer_in<&LayerDesc::wblk_base>(ws.desc, l0, l1, blk);
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER) return;
     const uint32_t wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
@@ -2084,7 +2107,7 @@ int select_impl(const adacomp_layer_t *layers, uint32_t L, double rate, const ui
         for (const Group &g : plan.groups) {
             if (!g.filters) continue;
             const uint32_t w0 = plan.desc[g.l0].wblk_base, g0 = plan.desc[g.l0].gblk_base;
-            LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, plan.desc[g.l1].wblk_base - w0, ws, Lp, w0);
+            LAUNCH(ADACOMP_KERNEL_FILTER, k_filter, plan.desc[g.l1].wblk_base - w0, ws, g.l0, g.l1, w0);
             // per tensor: finished on the spot, or checked and left to the kernels below
             ADACOMP_LAUNCH(ADACOMP_KERNEL_FINISH, k_finish, dim3(g.l1 - g.l0), dim3(SBLOCK), s, ws, g.l0, out_idx, out_val);
             if (hipGetLastError() != hipSuccess) return ADACOMP_ERR_HIP;
