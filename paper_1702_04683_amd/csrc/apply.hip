@@ -47,7 +47,7 @@ constexpr uint32_t BLOCK = 256;
 constexpr uint32_t WAVES = BLOCK / WAVE;
 constexpr uint32_t ITEMS = 4;          // scatter plan: entries per thread
 constexpr uint32_t TILE_MAX = 2048;    // sweep plan: most coordinates per tile of the sorting kernels (power of two); dense queues get smaller tiles
-constexpr uint32_t TILE_MAX_SPARSE = 4096;  // ... and of the kernel for sparse queues
+constexpr uint32_t TILE_MAX_SPARSE = 2048;  // ... and of the kernel for sparse queues
 constexpr uint32_t HOT_TILE_MAX = TILE_MAX_SPARSE;  // largest tile the kernel for overflowing tiles keeps in LDS
 constexpr uint32_t STAGE_CAP = 512;    // sweep plan: entries of the whole queue a tile can hold in LDS
 constexpr uint32_t SLOW_GRID = 1024;
@@ -241,7 +241,18 @@ struct Sweep {
 };
 
 __device__ __forceinline__ uint32_t tile_layer(const ParamDesc *P, uint32_t L, uint32_t t) {
-    uint32_t lo = 0, hi = L;  // the last l with tile_base[l] <= t
+    uint32_t lo = 0, hi = L;  // the last l with tile_base[l] <= t; t < tile_base[L], the number of tiles
+    {   // first probe by proportion: the answer when the tensors are equally large
+        uint32_t g = (uint32_t)((float)t * (float)L / (float)P[L].tile_base);
+        if (g >= L) g = L - 1;
+        const uint64_t b_g = P[g].tile_base, b_next = P[g + 1].tile_base;
+        if (b_g <= t) {
+            if (b_next > t) return g;
+            lo = g + 1;  // tile_base[g + 1] <= t
+        } else {
+            hi = g;
+        }
+    }
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
         if (P[mid].tile_base <= t) lo = mid; else hi = mid;
@@ -249,7 +260,9 @@ __device__ __forceinline__ uint32_t tile_layer(const ParamDesc *P, uint32_t L, u
     return lo;
 }
 
-// B[q][t] by bisection in the sorted index list of the tile's tensor; tile_tensor[t].
+constexpr uint32_t BOUNDS_WAYS = 4;
+
+// B[q][t] by search in the sorted index list of the tile's tensor; tile_tensor[t].
 __global__ __launch_bounds__(BLOCK) void k_bounds(Sweep sw, uint32_t *B, uint32_t *tile_tensor) {
     const uint64_t g = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
     const uint64_t per = (uint64_t)sw.ntiles + 1;
@@ -263,7 +276,21 @@ __global__ __launch_bounds__(BLOCK) void k_bounds(Sweep sw, uint32_t *B, uint32_
     const uint32_t l = tile_layer(sw.P, sw.L, t);
     if (q == 0) tile_tensor[t] = l;
     const uint32_t c0 = (t - (uint32_t)sw.P[l].tile_base) << sw.tile_shift;
-    uint64_t lo = u.off[l], hi = u.off[l + 1];
+    // The kernel is bound by the length of its chain of dependent loads: BOUNDS_WAYS - 1 probes per round, loaded
+    // together, cut the range into BOUNDS_WAYS parts, so log(n)/log(BOUNDS_WAYS) rounds instead of log2(n).
+    uint64_t lo = u.off[l], hi = u.off[l + 1];  // the answer lies in [lo, hi]
+    while (hi - lo >= BOUNDS_WAYS) {
+        const uint64_t step = (hi - lo) / BOUNDS_WAYS;  // >= 1
+        uint32_t v[BOUNDS_WAYS - 1];
+#pragma unroll
+        for (uint32_t j = 0; j < BOUNDS_WAYS - 1; ++j) v[j] = u.idx[lo + (j + 1) * step];  // positions < hi
+        uint32_t below = 0;  // probes with a smaller index: a prefix of them when the list is sorted
+#pragma unroll
+        for (uint32_t j = 0; j < BOUNDS_WAYS - 1; ++j) below += v[j] < c0 ? 1u : 0u;
+        const uint64_t base = lo;
+        if (below) lo = base + below * step + 1;                       // idx[base + below * step] < c0
+        if (below < BOUNDS_WAYS - 1) hi = base + (below + 1) * step;   // idx[that] >= c0
+    }
     while (lo < hi) {
         const uint64_t mid = lo + ((hi - lo) >> 1);
         if (u.idx[mid] < c0) lo = mid + 1; else hi = mid;
