@@ -50,7 +50,8 @@ namespace adacomp {
 namespace {
 
 constexpr uint32_t WSEG = 8192;     // elements per wave segment
-constexpr int FILTER_NLOAD = 2;     // 16-byte loads per lane in flight in the filter (measured best: 2, then 1, then 4)
+constexpr int FILTER_NLOAD = 1;     // 16-byte loads per lane in flight in the filter: at 8 waves per SIMD one keeps 32 KB per compute unit
+                                    // in flight, which is what the memory system takes; two are 3 % slower, half the waves 25 %
 constexpr uint32_t PIECE = 256;     // elements per wave-wide float4 load
 constexpr uint32_t BINS = 4096;     // histogram bins (12 key bits)
 constexpr uint32_t VCHUNK = 2048;   // packed candidates per wave chunk (descent, count, emit)
