@@ -26,6 +26,16 @@ __device__ __forceinline__ uint32_t popc64(uint64_t m) { return (uint32_t)__popc
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// The card hands the workgroups of a launch to its 8 XCDs (each with an L2 of its own) in turn.
+// For kernels whose consecutive workgroups read consecutive memory this gives every XCD one
+// contiguous eighth of the launch instead of every eighth piece: position in the launch of
+// the calling workgroup (a bijection of 0 .. gridDim.x - 1 whatever the real hand-out is).
+constexpr uint32_t XCDS = 8;
+__device__ __forceinline__ uint32_t xcd_contiguous_block() {
+    const uint32_t q = gridDim.x / XCDS, r = gridDim.x % XCDS, x = blockIdx.x % XCDS, i = blockIdx.x / XCDS;
+    return x * q + (x < r ? x : r) + i;
+}
+
 // Exclusive prefix sum of x over a workgroup of NWAVES full waves; `total` receives the
 // sum.  s_wave: NWAVES words of LDS, free for reuse when the call returns.
 template <uint32_t NWAVES>

@@ -730,7 +730,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t l0, uint32_t l1, uint32_t blk0) {
     __shared__ uint2 s_stage[WAVES][FSTAGE];
-    const uint32_t blk = blk0 + blockIdx.x;  // workgroup number across all groups of tensors; the launch covers tensors [l0, l1)
+    const uint32_t blk = blk0 + xcd_contiguous_block();  // workgroup number across all groups of tensors; the launch covers tensors [l0, l1)
     const uint32_t l = find_layer_in<&LayerDesc::wblk_base>(ws.desc, l0, l1, blk);
     const LayerDesc d = ws.desc[l];
     if (d.mode != MODE_FILTER) return;
