@@ -75,7 +75,7 @@ constexpr uint32_t FUSE_MAX_SEG = 2048;      // most segments of such a tensor (
 constexpr uint32_t FUSE_MAX_CAND = 1u << 17; // ... and most candidates the plan expects for it (the kernel accepts twice as many)
 constexpr uint32_t FUSE_MAX_CAP = 320;       // ... and largest region: fuller segments are packed faster by the gather's many waves
 constexpr uint32_t FUSE_SHIFT = 11;          // key bits resolved by its second histogram; the first takes the 12 above
-constexpr uint32_t FUSE_ROWS = 16;           // rows of 64 candidates that a packing wave of k_finish has in flight
+constexpr uint32_t FUSE_ROWS = 8;           // rows of 64 candidates that a packing wave of k_finish has in flight
 
 // Candidate regions of one group of tensors: consecutive tensors are filtered and finished (or
 // checked and packed) together, and the next group reuses the same region memory.  About a fifth
