@@ -153,6 +153,32 @@ def placement_experiment(ac, workloads, torch, dev, n_sets, rounds=3, steps=8):
     print(json.dumps({"experiment": "placement", "sets": n_sets, "elements_per_call": Q * sum(sizes), "results": res}), flush=True)
 
 
+def view_offset_experiment(ac, torch, dev, n=400_000_000, rate=0.005, reps=5):
+    """One tensor of n elements as a view that starts 0, 1, 2, 3, 8 and 33 elements into a buffer: select and filter time."""
+    gen = torch.Generator(device=dev).manual_seed(3)
+    base = torch.randn(n + 64, generator=gen, device=dev)
+    k = ac.adacomp_count(n, rate)
+    upd = ac.Update(1, k, dev)
+    ws = torch.empty(ac.adacomp_select_workspace([n], rate), dtype=torch.uint8, device=dev)
+    res = []
+    for shift in (0, 1, 2, 3, 8, 33):
+        layers = ac.Layers([base[shift:shift + n]])
+        for _ in range(2):
+            ac.adacomp_select(layers, rate, upd, ws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ac.adacomp_profile_start({"filter"})
+        e0.record()
+        for _ in range(reps):
+            ac.adacomp_select(layers, rate, upd, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms, _ = ac.adacomp_profile_stop()["filter"]
+        res.append({"offset_elements": shift, "offset_bytes": 4 * shift, "select_us": 1e3 * e0.elapsed_time(e1) / reps,
+                    "filter_us": 1e3 * ms / reps})
+    print(json.dumps({"experiment": "view offset", "elements": n, "rate": rate, "results": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -189,6 +215,9 @@ def main():
                     help="instead of the benchmark: allocate this many sets of 16 flat gradients (64 GB each) in one process, "
                          "time the same select call on each set in turn, three rounds, and print the filter time per set: "
                          "shows how much of the filter's run-to-run spread belongs to where the buffers lie in memory")
+    ap.add_argument("--view-offsets", action="store_true",
+                    help="instead of the benchmark: select on one 400M-element tensor that starts 0 to 33 elements into its "
+                         "buffer (a view into a flat parameter buffer), time per call and of the filter")
     ap.add_argument("--no-per-gradient", action="store_true",
                     help="skip the extra steps with one select call per worker gradient (flat workload)")
     ap.add_argument("--settle", type=float, default=None,
@@ -223,6 +252,9 @@ def main():
 
     if args.placement_sets > 0:
         placement_experiment(ac, workloads, torch, dev, args.placement_sets)
+        return
+    if args.view_offsets:
+        view_offset_experiment(ac, torch, dev)
         return
 
     nb = args.batches if args.batches else (3 if cfg == "flat" else 1)

@@ -624,6 +624,17 @@ __device__ __forceinline__ void lds_hist_add(uint32_t *h, const uint32_t (&key)[
     }
 }
 
+// Elements [lo, hi) of segment s of a tensor.  Segments are WSEG elements long; in a tensor that does
+// not start on a 128-byte boundary (a view into a flat buffer) the borders between them are moved to
+// the next such boundary (by the `head` < 32 elements in front of the tensor's first one), so that
+// only the tensor's first segment has a head to peel or loads that straddle cache lines.
+__device__ __forceinline__ void segment_range(const LayerDesc &d, uint32_t s, uint32_t &lo, uint32_t &hi) {
+    const uint32_t head = (uint32_t)((0u - (reinterpret_cast<uintptr_t>(d.g) >> 2)) & 31u);
+    const uint64_t b0 = s ? (uint64_t)s * WSEG + head : 0u, b1 = (uint64_t)(s + 1) * WSEG + head;
+    lo = b0 < d.n ? (uint32_t)b0 : d.n;
+    hi = (b1 < d.n && s + 1 < d.nseg) ? (uint32_t)b1 : d.n;  // the last segment ends with the tensor
+}
+
 // ---- step 1: sample histogram on the top 12 key bits -----------------------------
 __global__ __launch_bounds__(BLOCK) void k_sample_hist(Workspace ws, uint32_t L) {
     __shared__ uint32_t h[BINS];
@@ -742,8 +753,8 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t l0, uin
     uint2 *region = ws.cand + d.cand_base + (uint64_t)seg * d.cap;
     uint2 *stage = s_stage[wave];
     const uint32_t cap = d.cap;
-    const uint32_t lo = seg * WSEG;
-    const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
+    uint32_t lo, hi;
+    segment_range(d, seg, lo, hi);
     const Source src{reinterpret_cast<const uint32_t *>(d.g), nullptr, d.n, WSEG, d.vec != 0};
     uint32_t staged = 0;   // candidates in the stage (wave-uniform)
     uint32_t written = 0;  // candidates of this segment already flushed (may exceed cap: those are dropped)
@@ -985,8 +996,8 @@ __device__ __forceinline__ void gather_segments(const Workspace &ws, uint32_t l,
         const Source src{reinterpret_cast<const uint32_t *>(d.g), nullptr, d.n, WSEG, d.vec != 0};
         for (uint32_t i = 0; i < GS; ++i) {
             if (!((overflowed >> i) & 1u)) continue;
-            const uint32_t lo = (s0 + i) * WSEG;
-            const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
+            uint32_t lo, hi;
+            segment_range(d, s0 + i, lo, hi);
             uint32_t pos = __shfl(my_off, i);
             visit_range<false, false, 4>(src, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
                 bool f[4];
@@ -1550,8 +1561,8 @@ __global__ __launch_bounds__(SBLOCK) void k_finish(Workspace ws, uint32_t l0, ui
             while (over) {  // uniform
                 const uint32_t os = s0 + (uint32_t)__builtin_ctzll(over);
                 over &= over - 1;
-                const uint32_t lo = os * WSEG;
-                const uint32_t hi = d.n - lo < WSEG ? d.n : lo + WSEG;
+                uint32_t lo, hi;
+                segment_range(d, os, lo, hi);
                 uint32_t q0 = s_pre[os];
                 visit_range<false, false, 4>(dense, lo, hi, [&](const uint32_t(&idx)[4], const uint32_t(&bits)[4], uint32_t nvalid) {
                     bool f[4];
