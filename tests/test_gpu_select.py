@@ -168,12 +168,26 @@ def test_clustered_large_values_overflow_their_regions(ac, dev):
 
 
 def test_unaligned_tensor_views(ac, dev):
-    """Tensors that start 4, 8 or 12 bytes past a 16-byte boundary take the scalar load path."""
+    """Tensors that start 4, 8 or 12 bytes past a 16-byte boundary: only the elements in front of the
+    first boundary are read singly."""
     base = workloads.gradient_layer("cnn_select", 2, 4, 3211264, dev)
     views = [base[1:1_000_000], base[2:777_779], base[3:50_001], base[5:6]]
     assert all(v.data_ptr() % 16 != 0 for v in views)
     check(ac, [v for v in views], 0.01, what="unaligned")
     check(ac, [v for v in views], 0.4, what="unaligned dense")
+
+
+def test_views_at_any_offset_with_sizes_around_segment_borders(ac, dev):
+    """The borders between a tensor's 8192-element segments lie on 128-byte boundaries of its memory:
+    views that start 1 to 33 elements into a buffer, with sizes that leave the last segment empty,
+    nearly empty or full, selected by the filter pipeline (too large for the one-workgroup kernel)."""
+    base = workloads.gradient_layer("cnn_select", 2, 4, 3211264, dev)
+    whole = 40 * 8192
+    cases = [(1, 0), (1, 1), (3, 2), (3, 3), (4, 28), (8, 31), (31, 32), (33, 33), (2, 8191), (31, 1), (33, 30), (5, 8160)]
+    views = [base[o:o + whole + d] for o, d in cases]
+    assert all(v.numel() > (1 << 18) for v in views)
+    check(ac, views, 0.005, what="views around segment borders")
+    check(ac, views, 0.08, what="views around segment borders, dense")
 
 
 def test_negation_and_scaling_invariance_on_gpu(ac, dev):
