@@ -78,15 +78,15 @@ constexpr uint32_t FUSE_SHIFT = 11;          // key bits resolved by its second 
 constexpr uint32_t FUSE_ROWS = 8;           // rows of 64 candidates that a packing wave of k_finish has in flight
 
 // Candidate regions of one group of tensors: consecutive tensors are filtered and finished (or
-// checked and packed) together, and the next group reuses the same region memory.  About a fifth
-// of a region is written (its capacity is three times the expected fill), so the lines a group
-// really touches stay in the 256 MB last-level cache until they have been read, and are
-// overwritten there by the next group instead of travelling to HBM.  k_finish gives every tensor of
-// the group one workgroup: a group of more tensors than the chip has compute units takes two
-// rounds of them.  Measured on 16 x 4 GB gradients, filter launches per step: one group 11.3 ms,
-// 384 MB groups 10.6 ms, 768 MB groups 10.5 ms.
-constexpr uint64_t GROUP_BYTES = 768ull << 20;
-constexpr uint32_t GROUP_TENSORS = 256;
+// checked and packed) together, and the next group reuses the same region memory, which bounds the
+// workspace.  The filter writes the regions with streaming stores and k_finish gives every tensor of
+// the group one workgroup, in as many rounds as it takes; the tensors of a call are spread evenly
+// over the groups that these limits ask for.  Whole steps on 16 x 4 GB gradients (1600 tensors,
+// 5 GB of regions) on a settled box: 7 groups of up to 256 tensors 12.23 ms, 512 + 512 + 512 + 64
+// tensors 12.13, three groups of 534 12.18, 768 + 768 + 64 12.08, two groups of 800 12.03,
+// 1024 + 576 12.08, one group 12.13.
+constexpr uint64_t GROUP_BYTES = 2560ull << 20;
+constexpr uint32_t GROUP_TENSORS = 1024;
 
 enum : uint32_t { MODE_EMPTY = 0, MODE_IDENTITY = 1, MODE_FILTER = 2, MODE_DENSE = 3, MODE_SMALL = 4 };
 
@@ -348,6 +348,48 @@ int make_plan(const uint64_t *n, const float *const *data, uint32_t L, double ra
         return ADACOMP_ERR_LAYER_TOO_LARGE;
     grp.l1 = (uint32_t)plan.desc.size();
     plan.groups.push_back(grp);
+    if (plan.groups.size() > 1) {
+        // The pass above says how many groups the limits ask for.  The same number of groups with the
+        // filtered tensors spread evenly over them makes the launches equally long (1600 equal tensors:
+        // 800 + 800 instead of 1024 + 576); kept unless a group would then exceed the size limit.
+        const size_t ng = plan.groups.size();
+        uint32_t nf = 0;
+        for (const Group &g : plan.groups) nf += g.filters;
+        const uint32_t per = (uint32_t)((nf + ng - 1) / ng);
+        std::vector<Group> even;
+        std::vector<char> opens(plan.desc.size(), 0);
+        std::vector<uint64_t> base(plan.desc.size(), 0);
+        Group cur{0, 0, 0, 0};
+        uint64_t c = 0, c_max = 0;
+        bool fits = true;
+        for (uint32_t i = 0; i < plan.desc.size() && fits; ++i) {
+            const LayerDesc &d = plan.desc[i];
+            if (d.mode != MODE_FILTER) continue;
+            const uint64_t slots = (uint64_t)d.nseg * d.cap;
+            if (cur.filters >= per) {
+                cur.l1 = i;
+                even.push_back(cur);
+                cur = Group{i, i, 0, 0};
+                c = 0;
+                opens[i] = 1;
+            }
+            if (cur.filters && c + slots > group_slots_max) fits = false;
+            base[i] = c;
+            c += slots;
+            c_max = std::max(c_max, c);
+            ++cur.filters;
+            if (!d.fused) ++cur.unfused;
+        }
+        if (fits) {
+            cur.l1 = (uint32_t)plan.desc.size();
+            even.push_back(cur);
+            plan.groups = even;
+            plan.opens = opens;
+            for (uint32_t i = 0; i < plan.desc.size(); ++i)
+                if (plan.desc[i].mode == MODE_FILTER) plan.desc[i].cand_base = base[i];
+            cand_max = c_max;
+        }
+    }
     plan.off[L] = out;
     plan.desc.push_back(LayerDesc{});
     LayerDesc &e = plan.desc.back();
@@ -765,11 +807,16 @@ __global__ __launch_bounds__(BLOCK) void k_filter(Workspace ws, uint32_t l0, uin
         wave_lds_fence();
         const uint32_t n_out = last ? (staged + 15u) & ~15u : staged & ~15u;
         for (uint32_t e = lane; e < n_out; e += WAVE) {
-            // plain stores, not streaming ones: the finish (or gather) of the group reads the lines again within a
-            // millisecond, and the next group overwrites them in cache.  Measured on 16 x 4 GB gradients, one
-            // box, groups of 384 / 512 MB: finish 1.03 / 0.99 ms per step against 1.21 / 1.03 with non-temporal
-            // stores; the filter itself shows no difference beyond its run-to-run spread
-            if (written + e < cap) region[written + e] = stage[e];
+            // streaming stores: the lines are read once more, by the finish (or gather) of the group, and
+            // written whole.  Whole steps on a settled box: filter 9.28 against 9.61 ms with plain stores,
+            // finish 0.84 against 0.81 ms
+            if (written + e < cap) {
+                const uint2 t = stage[e];
+                u32x2 w;
+                w.x = t.x;
+                w.y = t.y;
+                __builtin_nontemporal_store(w, (__attribute__((address_space(1))) u32x2 *)&region[written + e]);
+            }
         }
         const uint32_t keep = last ? 0u : staged - n_out;  // < 16 entries move to the front
         uint2 moved = make_uint2(0, 0);
