@@ -706,7 +706,7 @@ __global__ __launch_bounds__(BLOCK) void k_sample_hist(Workspace ws, uint32_t L)
                 piece = q < d.npieces ? (uint32_t)q : d.npieces - 1;
             }
             first[j] = piece * PIECE + shift + lane * 4;
-            v[j] = load4(d.g, first[j], p < p_hi ? d.n : 0u, wide);
+            v[j] = load4<true>(d.g, first[j], p < p_hi ? d.n : 0u, wide);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
